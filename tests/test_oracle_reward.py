@@ -1,0 +1,157 @@
+"""Pins for the Draft Tree Reward (Eq. 2-5, ablation aggregates, App. A) and the greedy walk."""
+import math
+
+import numpy as np
+import pytest
+import scipy.special as sp
+
+import brute
+from oracle import gto_oracle as O
+
+
+def _case(seed, R, d, k, V, g, sigma=1.5):
+    rng = np.random.default_rng(seed)
+    D = rng.normal(0, sigma, size=(R, d, k, V))
+    T = rng.normal(0, sigma, size=(R, d, k, V))
+    st = O.draft_row_stats(D, k)
+    pool = O.expand_tree(st["top_tok"], st["top_logp32"], d, k, st["top_logp64"], st["top_logit"])
+    tree = O.select_topg(pool, g)
+    ts = O.target_row_stats(T)
+    return D, T, pool, tree, ts
+
+
+@pytest.mark.parametrize("seed,V,k,d,g", [(0, 4, 2, 3, 6), (1, 4, 3, 3, 12), (2, 5, 2, 3, 4), (3, 4, 2, 2, 6)])
+def test_nodesum_equals_enumeration_of_all_rollouts(seed, V, k, d, g):
+    D, T, pool, tree, ts = _case(seed, 2, d, k, V, g)
+    rew = O.tree_reward(tree, T, ts["t_lse"], 1.0)
+    for r in range(2):
+        kept, expanded = brute.build_tree(D[r], k, d, g)
+        paths = [p for p, _ in kept]
+        e_enum = brute.expected_accept_len_enumerate(paths, expanded, T[r], d)
+        e_rec = brute.expected_accept_len_recursive(paths, expanded, T[r])
+        assert abs(rew["reward_nodesum"][r] - e_enum) < 1e-12
+        assert abs(rew["reward_nodesum"][r] - e_rec) < 1e-12
+        # per-sequence expected acceptance lengths (Eq. 3-4) and their aggregates (Eq. 5, ablation)
+        Ls = brute.sequence_lengths(paths, expanded, T[r])
+        opaths = brute.oracle_paths(pool, tree, r)
+        got = {opaths[i]: rew["node_cum"][r, i] for i in range(int(tree["n_sel"][r])) if tree["sel_leaf"][r, i]}
+        assert set(got) == set(Ls)
+        for p in Ls:
+            assert abs(got[p] - Ls[p]) < 1e-12
+        vals = np.array(list(Ls.values()))
+        for eta in (1.0, 0.25, 4.0):
+            rr = O.tree_reward(tree, T, ts["t_lse"], eta)
+            assert abs(rr["reward_lse"][r] - sp.logsumexp(eta * vals) / eta) < 1e-12
+        assert abs(rew["reward_max"][r] - vals.max()) < 1e-15
+        assert abs(rew["reward_mean"][r] - vals.mean()) < 1e-13
+        assert rew["n_leaves"][r] == len(vals)
+
+
+def test_monte_carlo_rollouts_agree_with_nodesum():
+    D, T, pool, tree, ts = _case(5, 1, 3, 3, 12, 10, sigma=1.0)
+    rew = O.tree_reward(tree, T, ts["t_lse"], 1.0)
+    kept, expanded = brute.build_tree(D[0], 3, 3, 10)
+    keptset = set(p for p, _ in kept)
+    rng = np.random.default_rng(99)
+    n = 200000
+    lens = np.zeros(n)
+    probs = {node: brute.softmax64(T[0, lv, sl]) for node, (lv, sl) in expanded.items()}
+    for i in range(n):
+        node = ()
+        while node in probs:
+            tok = int(rng.choice(len(probs[node]), p=probs[node]))
+            if node + (tok,) not in keptset:
+                break
+            node = node + (tok,)
+        lens[i] = len(node)
+    se = lens.std() / math.sqrt(n)
+    assert abs(lens.mean() - rew["reward_nodesum"][0]) < 4 * se + 1e-9
+
+
+def test_closed_forms_constant_p_and_certain_target():
+    # target puts probability p on every kept token: L = p (1 - p^l) / (1 - p)
+    R, d, k, V, g = 1, 4, 2, 6, 8
+    D, _, pool, tree, _ = _case(8, R, d, k, V, g)
+    p = 0.4
+    n = int(tree["n_sel"][0])
+    T = np.zeros((R, d, k, V))
+    t_lse = np.zeros((R, d, k))            # pretend-normalised rows: log prob = log p for every token
+    T[:] = math.log(p)
+    rew = O.tree_reward(tree, T, t_lse, 1.0)
+    for i in range(n):
+        l = int(tree["sel_depth"][0, i])
+        assert abs(rew["node_cum"][0, i] - p * (1 - p ** l) / (1 - p)) < 1e-13
+        assert abs(rew["node_q"][0, i] - p ** l) < 1e-15
+    # all-ones target: L_i = l_i, nodesum = number of kept nodes (the upper bound of the reward)
+    T[:] = 0.0
+    rew = O.tree_reward(tree, T, t_lse, 1.0)
+    assert np.allclose(rew["node_cum"][0, :n], tree["sel_depth"][0, :n])
+    assert abs(rew["reward_nodesum"][0] - n) < 1e-12
+
+
+def test_bounds_and_single_sequence():
+    D, T, pool, tree, ts = _case(21, 8, 4, 3, 40, 15)
+    for eta in (0.5, 1.0, 3.0):
+        rew = O.tree_reward(tree, T, ts["t_lse"], eta)
+        N = rew["n_leaves"]
+        assert (rew["reward_max"] <= rew["reward_lse"] + 1e-12).all()           # App. A Eq. (1)
+        assert (rew["reward_lse"] <= rew["reward_max"] + np.log(N) / eta + 1e-12).all()
+        assert (rew["reward_nodesum"] <= tree["n_sel"] + 1e-12).all()            # reward <= kept nodes
+        assert (rew["reward_nodesum"] <= 4 + 1e-12).all()                        # and <= depth
+        assert (rew["reward_mean"] <= rew["reward_max"] + 1e-15).all()
+        assert (rew["reward_max"] <= rew["reward_nodesum"] + 1e-12).all()        # one branch is part of the union
+    # k = 1: one sequence, so LSE = max = mean = nodesum = L_1
+    rng = np.random.default_rng(4)
+    D1 = rng.normal(size=(2, 4, 1, 20)); T1 = rng.normal(size=(2, 4, 1, 20))
+    st = O.draft_row_stats(D1, 1)
+    pool = O.expand_tree(st["top_tok"], st["top_logp32"], 4, 1)
+    tree = O.select_topg(pool, 10)
+    ts = O.target_row_stats(T1)
+    rew = O.tree_reward(tree, T1, ts["t_lse"], 1.0)
+    for key in ("reward_max", "reward_mean", "reward_nodesum"):
+        np.testing.assert_allclose(rew["reward_lse"], rew[key], rtol=1e-13)
+
+
+def test_onehot_target_ties_reward_to_greedy_walk():
+    """App. A case (b): with a deterministic target every L_i is the common-prefix length
+    with the greedy trajectory and max_i L_i is the accepted length."""
+    rng = np.random.default_rng(17)
+    R, d, k, V, g = 12, 4, 3, 9, 14
+    D = rng.normal(0, 1.0, size=(R, d, k, V))
+    st = O.draft_row_stats(D, k)
+    pool = O.expand_tree(st["top_tok"], st["top_logp32"], d, k)
+    tree = O.select_topg(pool, g)
+    T = np.full((R, d, k, V), -np.inf)
+    # target's certain token: the draft's best token with prob 1/2, else a random token
+    for r in range(R):
+        for (l, j) in O.used_slots(d, k):
+            tok = int(st["top_tok"][r, l, j, 0]) if rng.random() < 0.6 else int(rng.integers(V))
+            T[r, l, j, tok] = 0.0
+    ts = O.target_row_stats(T)
+    rew = O.tree_reward(tree, T, ts["t_lse"], 1.0)
+    path = O.accepted_path(tree, ts["t_argmax"], d)
+    n = tree["n_sel"]
+    for r in range(R):
+        cum = rew["node_cum"][r, :n[r]]
+        assert np.all(np.abs(cum - np.round(cum)) < 1e-12)
+        assert abs(rew["reward_max"][r] - path["path_len"][r]) < 1e-12
+        assert abs(rew["reward_nodesum"][r] - path["path_len"][r]) < 1e-12
+        kept, expanded = brute.build_tree(D[r], k, d, g)
+        walk = brute.greedy_accept([p for p, _ in kept], expanded, T[r], d)
+        opaths = brute.oracle_paths(pool, tree, r)
+        assert [opaths[i] for i in path["path_node"][r, :path["path_len"][r]]] == [walk[:j + 1] for j in range(len(walk))]
+        # path_slot names the row that produced each step
+        for t in range(path["path_len"][r]):
+            node = walk[:t]
+            assert expanded[node] == (t, int(path["path_slot"][r, t]))
+        assert (path["path_node"][r, path["path_len"][r]:] == -1).all()
+    assert path["path_len"].max() >= 2      # the case really exercises multi-step walks
+
+
+def test_walk_stops_at_unexpanded_child_and_on_random_targets():
+    D, T, pool, tree, ts = _case(33, 10, 4, 3, 8, 20, sigma=2.5)
+    path = O.accepted_path(tree, ts["t_argmax"], 4)
+    for r in range(10):
+        kept, expanded = brute.build_tree(D[r], 3, 4, 20)
+        walk = brute.greedy_accept([p for p, _ in kept], expanded, T[r], 4)
+        assert path["path_len"][r] == len(walk)

@@ -1,0 +1,222 @@
+/*
+ * gto.h - C ABI of the MI355X (gfx950) implementation of the data-parallel core of
+ * Group Tree Optimization (GTO): batched draft-tree construction, the sampling-free
+ * Draft Tree Reward, group-standardised advantages and the clipped likelihood-ratio
+ * surrogate (forward and gradient w.r.t. the draft logits).
+ *
+ * Paper: "Bridging Draft Policy Misalignment: Group Tree Optimization for Speculative
+ * Decoding".  Each entry point cites the passage that defines what it computes.
+ *
+ * Conventions that hold for every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller; `cfg` and the small
+ *     structs that bundle pointers are HOST memory, read during the call only.
+ *   - The library never allocates, frees or keeps device memory, never synchronises, and
+ *     enqueues all work on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream).  Outputs are valid once that stream has reached the end of the call.
+ *   - Inputs are never modified.  Results are deterministic run to run.
+ *   - Return value: GTO_OK (0) or a negative gto_status.  Arguments are validated on the
+ *     host before anything is launched, so a failing call has no side effect.
+ *   - Logits are finite or -inf (probability 0).  A row that is entirely -inf, or holds a
+ *     NaN, gives unspecified results for that root (no fault).
+ *
+ * Shapes.  R roots, d levels, k branching, g kept nodes, V vocabulary,
+ * C = k + (d-1) k^2 generated candidates per root.
+ *   logits [R, d, k, row_stride] : slot (l, j) holds the next-token logits at the j-th
+ *       expanded node of level l (level 0 = the root, only slot (0,0) is used; slots
+ *       (0, 1..k-1) are padding and are never read).  Element type cfg->dtype.  Every row
+ *       starts 16-byte aligned (base pointer aligned, row_stride * sizeof(elem) % 16 == 0).
+ *   pool index c of a candidate: c = r for the root's r-th best child; for l >= 1 the
+ *       r-th best child of slot (l, j) is c = k + (l-1) k^2 + j k + r.
+ * Limits (GTO_E_SHAPE otherwise): 1 <= k <= 64, 1 <= d <= 32, C <= 4096, g >= 1, V >= k,
+ *       V < 2^31 - 64K, R * (1 + (d-1) k) < 2^31, R % group_size == 0 for the group-wise calls.
+ */
+#ifndef GTO_H
+#define GTO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gto_status {
+  GTO_OK = 0,
+  GTO_E_NULL = -1,      /* a required pointer is NULL                                   */
+  GTO_E_SHAPE = -2,     /* a size is outside the limits above                           */
+  GTO_E_ALIGN = -3,     /* logits base or row stride not 16-byte aligned                */
+  GTO_E_DTYPE = -4,     /* cfg->dtype is not GTO_BF16 / GTO_F32                         */
+  GTO_E_MODE = -5,      /* cfg->reward_mode unknown, or eta/eps/delta not usable        */
+  GTO_E_WORKSPACE = -6, /* workspace missing, misaligned or smaller than required       */
+  GTO_E_HIP = -7        /* a launch failed; gto_strerror(GTO_E_HIP) has the HIP message */
+} gto_status;
+
+enum { GTO_BF16 = 0, GTO_F32 = 1 };
+enum { GTO_REWARD_LSE = 0, GTO_REWARD_MAX = 1, GTO_REWARD_MEAN = 2, GTO_REWARD_NODESUM = 3 };
+enum { GTO_FLAG_GRAD_ZERO_FILL = 1 }; /* bwd also writes zeros into rows that carry no gradient */
+
+typedef struct gto_config {
+  int32_t R, d, k, g, V;
+  int32_t dtype;        /* element type of all logits tensors                              */
+  int64_t row_stride;   /* elements between consecutive rows, >= V                         */
+  int32_t group_size;   /* m of Eq. 6: consecutive roots per group                         */
+  int32_t reward_mode;  /* which aggregate feeds `reward` (all four are always computed)   */
+  float eta;            /* smooth-max temperature of Eq. 5 (paper: 1)                      */
+  float eps;            /* clip range of Eq. 12                                            */
+  float delta;          /* std floor of Eq. 10                                             */
+  float grad_scale;     /* upstream dL/dL_GTO (the paper's omega = 0.5 in Eq. 13)          */
+  int32_t flags;        /* GTO_FLAG_*                                                      */
+  int32_t reserved;     /* must be 0                                                       */
+} gto_config;
+
+/* Row statistics of a draft-logits tensor.  Entries of padding slots are not written. */
+typedef struct gto_draft_stats {
+  float *row_max;    /* [R, d, k]     max logit of the row                                  */
+  float *row_lse;    /* [R, d, k]     log sum exp of the row                                */
+  int32_t *top_tok;  /* [R, d, k, k]  k best tokens: logit descending, token id ascending   */
+  float *top_logp;   /* [R, d, k, k]  their log-probabilities (full-vocabulary softmax)     */
+} gto_draft_stats;
+
+typedef struct gto_target_stats {
+  float *t_max;      /* [R, d, k] */
+  float *t_lse;      /* [R, d, k] */
+  int32_t *t_argmax; /* [R, d, k] lowest token id attaining the max */
+} gto_target_stats;
+
+/* Candidate pool of one expansion, all [R, C] unless noted. */
+typedef struct gto_pool {
+  int32_t *cand_tok;
+  int32_t *cand_parent; /* pool index of the parent, -1 for depth-1 nodes                  */
+  int32_t *cand_depth;  /* 1..d                                                             */
+  int32_t *cand_pslot;  /* slot j (within level depth-1) of the parent                      */
+  int32_t *cand_slot;   /* slot the node itself occupies at level depth if expanded, else -1 */
+  float *cand_score;    /* cumulative draft log-probability from the root (fp32 adds)       */
+  int32_t *slot_cand;   /* [R, d, k] pool index expanded in each slot; level 0: -1          */
+} gto_pool;
+
+/* Kept tree, all [R, g]; positions >= n_sel hold -1 (ints) / 0 (score). */
+typedef struct gto_tree {
+  int32_t *sel_cand;   /* pool index                                                       */
+  int32_t *sel_tok;
+  int32_t *sel_parent; /* position of the parent in this list, -1 for depth-1 nodes        */
+  int32_t *sel_depth;
+  int32_t *sel_pslot;
+  int32_t *sel_slot;
+  int32_t *sel_leaf;   /* 1 if no kept child                                               */
+  float *sel_score;
+  int32_t *n_sel;      /* [R] = min(g, C)                                                  */
+} gto_tree;
+
+typedef struct gto_reward {
+  float *node_q;       /* [R, g] target probability that the path up to the node is accepted */
+  float *node_cum;     /* [R, g] sum of node_q along the path = L of Eq. 3 at a leaf        */
+  float *reward;       /* [R]    the aggregate chosen by cfg->reward_mode                   */
+  float *reward_aux;   /* [R, 4] lse (Eq. 5), max, mean, nodesum, in GTO_REWARD_* order     */
+  int32_t *n_leaves;   /* [R]    number of root-to-leaf sequences N                         */
+  int32_t *path_len;   /* [R]    length l of the longest accepted sequence, 0..d            */
+  int32_t *path_node;  /* [R, d] its nodes as positions in the kept list, -1 beyond l       */
+  int32_t *path_slot;  /* [R, d] slot (within level t) of the node whose row produced step t */
+} gto_reward;
+
+typedef struct gto_ppo {
+  float *logM;        /* [R] log-probability of the accepted sequence under the current draft */
+  float *logM0;       /* [R] ... under the reference draft                                  */
+  float *ratio;       /* [R] s_i of Eq. 11                                                  */
+  float *term;        /* [R] min(s A, clip(s) A)                                            */
+  int32_t *active;    /* [R] 1 if a gradient flows (l > 0 and the unclipped branch is the min) */
+  float *coef;        /* [R] c_i multiplying (onehot - softmax) in the backward             */
+  float *loss_group;  /* [R / group_size] Eq. 12 per group                                  */
+  float *loss;        /* [1] mean of the group losses                                       */
+} gto_ppo;
+
+int gto_version(void);
+/* Static text for a status; for GTO_E_HIP the text of the last HIP error seen by this thread. */
+const char *gto_strerror(int status);
+/* Host only.  Bytes of device workspace the calls below may need for `cfg` (256-byte aligned). */
+int gto_workspace_bytes(const gto_config *cfg, size_t *bytes_out);
+
+/* Per-row statistics of draft logits: max, log-sum-exp, and the k most probable tokens with
+ * their log-probabilities under the full-vocabulary softmax (Fig. 1 caption: the number on an
+ * edge is the draft probability of that token; App. B.3: top-k per node, k = 10).  One pass
+ * over every used row. */
+int gto_draft_row_stats(const gto_config *cfg, const void *draft_logits,
+                        const gto_draft_stats *stats_out, void *hip_stream);
+
+/* Per-row statistics of target logits needed by Eq. 3-4 and by greedy verification. */
+int gto_target_row_stats(const gto_config *cfg, const void *target_logits,
+                         const gto_target_stats *stats_out, void *hip_stream);
+
+/* Stage (i) of the decoding policy G (Sec. 3.1, "Layer-wise expansion"; Fig. 1 caption for
+ * the score): gto_draft_row_stats, then the level-by-level expansion.  A candidate's global
+ * acceptance score is score(parent) + log-probability (fp32 add; root = 0); at every level
+ * below the last the k best of the k^2 children (score descending, pool index ascending)
+ * become the next level's slots, in that order. */
+int gto_expand_tree(const gto_config *cfg, const void *draft_logits,
+                    const gto_draft_stats *stats_out, const gto_pool *pool_out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The expansion alone, from row statistics already on the device. */
+int gto_expand_from_stats(const gto_config *cfg, const gto_draft_stats *stats,
+                          const gto_pool *pool_out, void *hip_stream);
+
+/* Stage (ii) of G (Sec. 3.1, "Global pruning and re-ranking"; App. B.1: budget of 60
+ * draft tokens): rank all C candidates by (score descending, pool index ascending), keep the
+ * first min(g, C) in that order, remap parents, flag leaves. */
+int gto_select_topg(const gto_config *cfg, const gto_pool *pool, const gto_tree *tree_out,
+                    void *hip_stream);
+
+/* Draft Tree Reward (Eq. 2-5; Max / Mean of the aggregation ablation; App. A Eq. (2) as
+ * `nodesum`) and the longest accepted sequence under greedy target verification (Sec. 3.2,
+ * Algorithm 1; App. A case T = 0).  Runs gto_target_row_stats, then the per-root scan. */
+int gto_tree_reward(const gto_config *cfg, const gto_tree *tree, const void *target_logits,
+                    const gto_target_stats *stats_out, const gto_reward *reward_out,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The per-root reward scan alone, from target statistics already on the device. */
+int gto_reward_from_stats(const gto_config *cfg, const gto_tree *tree, const void *target_logits,
+                          const gto_target_stats *stats, const gto_reward *reward_out,
+                          void *hip_stream);
+
+/* Eq. 9-10: adv = (Rdeb - mean) / (std + delta) within groups of cfg->group_size consecutive
+ * roots, Rdeb = reward_cur - reward_ref, population std.  reward_ref == NULL skips the
+ * debiasing (the paper's "w/o Debiasing" ablation). */
+int gto_group_advantage(const gto_config *cfg, const float *reward_cur, const float *reward_ref,
+                        float *adv_out, void *hip_stream);
+
+/* Eq. 11-12 on the longest accepted sequence of the current tree.  `ref_logits_on_cur` holds
+ * the reference draft model's logits at the same slot coordinates as `draft_logits_cur`.
+ * `ref_stats` may be NULL: then the log-sum-exp of the (at most d) reference rows on each path
+ * is computed here into `workspace`. */
+int gto_ppo_surrogate_fwd(const gto_config *cfg, const gto_tree *tree_cur,
+                          const gto_reward *path_cur, const void *draft_logits_cur,
+                          const gto_draft_stats *draft_stats_cur, const void *ref_logits_on_cur,
+                          const gto_draft_stats *ref_stats, const float *adv,
+                          const gto_ppo *out, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+
+/* Gradient of cfg->grad_scale * loss w.r.t. the current draft logits (derivative of Eq. 11-12
+ * with the advantage and the tree held constant): for step t < l_i of root i,
+ *   grad_rows[i, t, v] = coef_i * (1[v == token_t] - softmax(row)[v]),
+ * the row being slot grad_slot[i, t] of level t.  grad_rows is [R, d, V] fp32 (dense, row
+ * length V); grad_slot is [R, d], -1 where the row carries no gradient (t >= l_i or
+ * coef_i == 0).  Such rows are left untouched unless GTO_FLAG_GRAD_ZERO_FILL is set. */
+int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur,
+                          const gto_reward *path_cur, const gto_ppo *fwd,
+                          const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
+                          float *grad_rows, int32_t *grad_slot, void *hip_stream);
+
+/* Tuning knob: wavefronts that share one logits row in the row kernels (1, 2, 4 or 8; other
+ * values select the default 4).  Process-wide; returns the value in effect. */
+int gto_set_waves_per_row(int waves);
+
+/* Optional per-kernel timing.  While enabled, every kernel launch of the calling thread is
+ * bracketed by HIP events on its stream.  gto_profile_read synchronises those events and
+ * returns, for up to `cap` distinct kernels, the name, the number of launches and the summed
+ * duration in milliseconds since the last read; it returns the number of kernels written. */
+int gto_profile_enable(int on);
+int gto_profile_read(const char **names, int32_t *launches, double *total_ms, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GTO_H */

@@ -1,0 +1,16 @@
+"""MI355X-native core of Group Tree Optimization: thin Python binding over libgto.so.
+
+The binding only marshals arguments (torch tensors -> device pointers, current stream);
+every step of the path runs in the HIP kernels of libgto.so.  There is no CPU fallback:
+if the library is missing, importing the binding's entry points raises.
+"""
+from .binding import (  # noqa: F401
+    GTO_BF16, GTO_F32, GTO_REWARD_LSE, GTO_REWARD_MAX, GTO_REWARD_MEAN, GTO_REWARD_NODESUM,
+    GTO_FLAG_GRAD_ZERO_FILL, GtoError, make_config, lib, lib_path,
+    alloc_draft_stats, alloc_target_stats, alloc_pool, alloc_tree, alloc_reward, alloc_ppo,
+    gto_version, gto_strerror, gto_workspace_bytes,
+    gto_draft_row_stats, gto_target_row_stats, gto_expand_tree, gto_expand_from_stats,
+    gto_select_topg, gto_tree_reward, gto_reward_from_stats, gto_group_advantage,
+    gto_ppo_surrogate_fwd, gto_ppo_surrogate_bwd, gto_set_waves_per_row,
+    gto_profile_enable, gto_profile_read,
+)

@@ -1,0 +1,91 @@
+// Kernel argument blocks and host-side launchers (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gto {
+
+struct RowStatsArgs {
+  const void *logits;
+  int64_t row_stride;
+  int V, d, kslots, ktop, rho;
+  const int32_t *path_slot;  // null: all used slots; else rows (root, step) on an accepted path
+  float *row_max;            // may be null
+  float *row_lse;
+  int32_t *top_tok;          // may be null (then no top-k output)
+  float *top_logp;           // may be null
+};
+
+struct PpoBwdArgs {
+  const void *logits;
+  int64_t row_stride;
+  int V, d, k, g;
+  const int32_t *path_slot, *path_node, *sel_tok;
+  const float *coef, *row_lse;
+  float *grad_rows;
+  int32_t *grad_slot;
+  int zero_fill;
+};
+
+struct ExpandArgs {
+  int R, d, k, C;
+  const int32_t *top_tok;
+  const float *top_logp;
+  int32_t *cand_tok, *cand_parent, *cand_depth, *cand_pslot, *cand_slot;
+  float *cand_score;
+  int32_t *slot_cand;
+};
+
+struct SelectArgs {
+  int R, C, g;
+  const int32_t *cand_tok, *cand_parent, *cand_depth, *cand_pslot, *cand_slot;
+  const float *cand_score;
+  int32_t *sel_cand, *sel_tok, *sel_parent, *sel_depth, *sel_pslot, *sel_slot, *sel_leaf;
+  float *sel_score;
+  int32_t *n_sel;
+};
+
+struct RewardArgs {
+  int R, d, k, g, dtype, reward_mode;
+  int64_t row_stride;
+  float eta;
+  const void *target_logits;
+  const float *t_lse;
+  const int32_t *t_argmax;
+  const int32_t *sel_tok, *sel_parent, *sel_depth, *sel_pslot, *sel_slot, *sel_leaf, *n_sel;
+  float *node_q, *node_cum, *reward, *reward_aux;
+  int32_t *n_leaves, *path_len, *path_node, *path_slot;
+};
+
+struct AdvArgs {
+  int R, m;
+  float delta;
+  const float *r_cur, *r_ref;  // r_ref may be null
+  float *adv;
+};
+
+struct PpoFwdArgs {
+  int R, d, k, g, m, dtype;
+  int64_t row_stride;
+  float eps, grad_scale;
+  const void *draft_logits, *ref_logits;
+  const float *draft_lse;   // [R, d, k]
+  const float *ref_lse;     // [R, d, k] if ref_lse_by_step == 0, else [R, d]
+  int ref_lse_by_step;
+  const int32_t *sel_tok, *path_len, *path_node, *path_slot;
+  const float *adv;
+  float *logM, *logM0, *ratio, *term, *coef, *loss_group, *loss;
+  int32_t *active;
+};
+
+void set_waves_per_row(int w);
+int get_waves_per_row();
+void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st);
+void launch_ppo_bwd(const PpoBwdArgs &a, int dtype, int blocks, hipStream_t st);
+void launch_expand(const ExpandArgs &a, hipStream_t st);
+void launch_select(const SelectArgs &a, hipStream_t st);
+void launch_reward(const RewardArgs &a, hipStream_t st);
+void launch_advantage(const AdvArgs &a, hipStream_t st);
+void launch_ppo_fwd(const PpoFwdArgs &a, hipStream_t st);
+
+}  // namespace gto

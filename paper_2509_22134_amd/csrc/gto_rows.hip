@@ -1,0 +1,325 @@
+// Row-streaming kernels of the GTO hot path (gfx950, wave64).
+//
+//  k_row_stats : one workgroup per logits row.  Streams the row once with 16-byte loads and
+//                produces max, log-sum-exp and the exact top-k (value descending, token id
+//                ascending).  Used for draft rows (k = branching), target rows (k = 1 gives
+//                the argmax) and for the reference rows on an accepted path.
+//  k_ppo_bwd   : one workgroup per (root, path step).  Re-streams one draft row and writes
+//                one fp32 gradient row  coef * (onehot - softmax).
+//
+// Both are HBM-bandwidth bound by design: per element they spend one conversion, one fused
+// multiply-add, one exp2 and one add; the top-k costs one max per element plus a rarely
+// taken insertion path.
+#include "gto_device.h"
+#include "gto_kernels.h"
+
+namespace gto {
+
+// ----------------------------------------------------------------------------- top-k list
+// A wave keeps the 64 best (value, id) pairs it has seen, sorted, one per lane (lane 0 = best).
+// Inserting shifts the tail down by one lane with a single DPP move per register.
+struct TopList {
+  float v;
+  int id;
+  __device__ __forceinline__ void init() { v = neg_inf(); id = kNoId; }
+  __device__ __forceinline__ void insert(float cv, int ci) {
+    const bool b = better(cv, ci, v, id);
+    const float uv = wave_shr1(v, __builtin_inff());
+    const int ui = wave_shr1(id, -1);
+    const bool bu = better(cv, ci, uv, ui);
+    v = b ? (bu ? uv : cv) : v;
+    id = b ? (bu ? ui : ci) : id;
+  }
+};
+
+// k-th largest of the 64 per-lane values (k <= 64), the same in every lane.
+__device__ __forceinline__ float kth_largest_of_lanes(float x, int k) {
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kWave; ++i) cnt += (readlane(x, i) > x) ? 1 : 0;
+  float cand = (cnt < k) ? x : __builtin_inff();
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) cand = fminf(cand, __shfl_xor(cand, off, kWave));
+  return cand;
+}
+
+// Per-lane streaming state: running max m, log2-domain offset c = m*log2(e) and
+// s = sum 2^(x*log2(e) - c) over the elements this lane has seen.
+struct LaneAcc {
+  float m, c, s;
+  __device__ __forceinline__ void init() { m = neg_inf(); c = 0.f; s = 0.f; }
+};
+
+template <typename T, int LOADS, bool GUARD>
+__device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_base, int V, int lane,
+                                          int ktop, bool &first, LaneAcc &acc, TopList &top,
+                                          float &thr_v, int &thr_i) {
+  constexpr int EPV = Elem<T>::kPerVec;
+  float x[LOADS][EPV];
+  u32x4 q[LOADS];
+#pragma unroll
+  for (int u = 0; u < LOADS; ++u) {
+    const int e0 = tile_base + (u * kWave + lane) * EPV;
+    if (!GUARD || e0 < V) {
+      q[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + e0));
+    } else {
+      q[u] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < LOADS; ++u) {
+    Elem<T>::unpack(q[u], x[u]);
+    if (GUARD) {
+      const int e0 = tile_base + (u * kWave + lane) * EPV;
+#pragma unroll
+      for (int e = 0; e < EPV; ++e)
+        if (e0 + e >= V) x[u][e] = neg_inf();
+    }
+  }
+  float cm = x[0][0];
+#pragma unroll
+  for (int u = 0; u < LOADS; ++u)
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) cm = fmaxf(cm, x[u][e]);
+
+  // online log-sum-exp in the log2 domain
+  const float m_new = fmaxf(acc.m, cm);
+  const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
+  const float scale = __builtin_amdgcn_exp2f(acc.c - c_new);
+  float s = (acc.m == neg_inf()) ? 0.f : acc.s * scale;
+#pragma unroll
+  for (int u = 0; u < LOADS; ++u)
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][e], kLog2e, -c_new));
+  acc.m = m_new;
+  acc.c = c_new;
+  acc.s = s;
+
+  // top-k: first tile of a wave seeds the threshold with the k-th largest lane maximum, a
+  // value that at least k elements of this tile reach.
+  if (first) {
+    first = false;
+    thr_v = kth_largest_of_lanes(cm, ktop);
+    thr_i = kNoId;
+  }
+  const int lane_first = tile_base + lane * EPV;
+  const bool hit = better(cm, lane_first, thr_v, thr_i);
+  if (__builtin_amdgcn_ballot_w64(hit) == 0) return;
+
+#pragma unroll
+  for (int u = 0; u < LOADS; ++u) {
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) {
+      const int my_id = tile_base + (u * kWave + lane) * EPV + e;
+      bool p = better(x[u][e], my_id, thr_v, thr_i);
+      if (GUARD) p = p && (my_id < V);
+      uint64_t mask = __builtin_amdgcn_ballot_w64(p);
+      while (mask) {
+        const int src = __builtin_ctzll(mask);
+        mask &= mask - 1;
+        const float cv = readlane(x[u][e], src);
+        const int ci = tile_base + (u * kWave + src) * EPV + e;
+        if (better(cv, ci, thr_v, thr_i)) {
+          top.insert(cv, ci);
+          const float nv = readlane(top.v, ktop - 1);
+          const int ni = readlane(top.id, ktop - 1);
+          if (better(nv, ni, thr_v, thr_i)) {
+            thr_v = nv;
+            thr_i = ni;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int WAVES, int LOADS>
+__global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
+  constexpr int EPV = Elem<T>::kPerVec;
+  constexpr int TILE = kWave * LOADS * EPV;
+  const int lane = lane_id();
+  const int wave = threadIdx.x / kWave;
+
+  // which row
+  int r, l, j;
+  int64_t oi;
+  if (a.path_slot == nullptr) {
+    r = blockIdx.x / a.rho;
+    const int qq = blockIdx.x - r * a.rho;
+    l = (qq == 0) ? 0 : 1 + (qq - 1) / a.kslots;
+    j = (qq == 0) ? 0 : (qq - 1) % a.kslots;
+    oi = stat_index(r, l, j, a.d, a.kslots);
+  } else {  // rows on an accepted path: block = (root, step)
+    r = blockIdx.x / a.d;
+    l = blockIdx.x - r * a.d;
+    j = a.path_slot[(int64_t)r * a.d + l];
+    if (j < 0) return;
+    oi = (int64_t)r * a.d + l;
+  }
+  const T *row = static_cast<const T *>(a.logits) + stat_index(r, l, j, a.d, a.kslots) * a.row_stride;
+  const int V = a.V;
+
+  LaneAcc acc;
+  acc.init();
+  TopList top;
+  top.init();
+  float thr_v = neg_inf();
+  int thr_i = kNoId;
+  bool first = true;
+
+  const int n_full = V / TILE;
+  for (int t = wave; t < n_full; t += WAVES)
+    scan_tile<T, LOADS, false>(row, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+  if (n_full * TILE < V && (n_full % WAVES) == wave)
+    scan_tile<T, LOADS, true>(row, n_full * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+
+  // wave-level reduction of (max, offset, sum)
+  const float Mw = wave_max(acc.m);
+  const float Cw = wave_max(acc.m == neg_inf() ? neg_inf() : acc.c);
+  const double contrib =
+      (acc.m == neg_inf()) ? 0.0 : (double)acc.s * (double)__builtin_amdgcn_exp2f(acc.c - Cw);
+  const double Sw = wave_sum(contrib);
+
+  __shared__ float sh_v[WAVES * kWave];
+  __shared__ int sh_i[WAVES * kWave];
+  __shared__ float sh_M[WAVES], sh_C[WAVES];
+  __shared__ double sh_S[WAVES];
+  __shared__ double sh_lse;
+  sh_v[threadIdx.x] = top.v;
+  sh_i[threadIdx.x] = top.id;
+  if (lane == 0) {
+    sh_M[wave] = Mw;
+    sh_C[wave] = Cw;
+    sh_S[wave] = Sw;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float M = sh_M[0], C = sh_C[0];
+    bool any = (sh_M[0] != neg_inf());
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+      M = fmaxf(M, sh_M[w]);
+      if (sh_M[w] != neg_inf()) {
+        C = any ? fmaxf(C, sh_C[w]) : sh_C[w];
+        any = true;
+      }
+    }
+    double S = 0.0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w)
+      if (sh_M[w] != neg_inf()) S += sh_S[w] * (double)__builtin_amdgcn_exp2f(sh_C[w] - C);
+    // log2-domain total is C + log2(S); the row maximum contributes exactly M*log2e of it.
+    const double lse = (double)M + kLn2 * (((double)C - (double)M * (double)kLog2e) + log2(S));
+    sh_lse = lse;
+    if (a.row_max) a.row_max[oi] = M;
+    a.row_lse[oi] = (float)lse;
+  }
+  if (a.top_tok == nullptr) return;
+  __syncthreads();
+  // merge the WAVES sorted lists: rank each of the first ktop entries of every wave
+  if (lane < a.ktop) {
+    const float v = top.v;
+    const int id = top.id;
+    int rank = 0;
+    for (int w = 0; w < WAVES; ++w)
+      for (int i = 0; i < a.ktop; ++i) rank += better(sh_v[w * kWave + i], sh_i[w * kWave + i], v, id) ? 1 : 0;
+    if (rank < a.ktop && id != kNoId) {
+      a.top_tok[oi * a.ktop + rank] = id;
+      if (a.top_logp) a.top_logp[oi * a.ktop + rank] = (float)((double)v - sh_lse);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- backward
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
+  const int r = blockIdx.x / a.d;
+  const int t = blockIdx.x - r * a.d;
+  const int64_t rt = (int64_t)r * a.d + t;
+  const int j = a.path_slot[rt];
+  const float coef = a.coef[r];
+  const bool valid = (j >= 0) && (coef != 0.f);
+  if (threadIdx.x == 0) a.grad_slot[rt] = valid ? j : -1;
+  float *__restrict__ out = a.grad_rows + rt * (int64_t)a.V;
+  const int V = a.V;
+  if (!valid) {
+    if (a.zero_fill) {
+      if (VEC) {
+        f32x4 *o4 = reinterpret_cast<f32x4 *>(out);
+        for (int i = threadIdx.x; i < V / 4; i += blockDim.x) o4[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      } else {
+        for (int i = threadIdx.x; i < V; i += blockDim.x) out[i] = 0.f;
+      }
+    }
+    return;
+  }
+  const int tok = a.sel_tok[(int64_t)r * a.g + a.path_node[rt]];
+  const float lse = a.row_lse[stat_index(r, t, j, a.d, a.k)];
+  const T *__restrict__ row = static_cast<const T *>(a.logits) + stat_index(r, t, j, a.d, a.k) * a.row_stride;
+  if (VEC) {
+    // four elements per lane per step: one 8- or 16-byte load, one 16-byte store
+    const int n4 = V / 4;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+      float x[4];
+      if (sizeof(T) == 2) {
+        const u32x2 q = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(row) + i);
+        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
+        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
+      } else {
+        const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + i);
+        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
+        x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+      }
+      float gq[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float p = __builtin_amdgcn_exp2f((x[e] - lse) * kLog2e);
+        gq[e] = -coef * p;
+        if (i * 4 + e == tok) gq[e] += coef;
+      }
+      const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
+      __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
+    }
+  } else {
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+      const float xv = Elem<T>::load1(row + i);
+      const float p = __builtin_amdgcn_exp2f((xv - lse) * kLog2e);
+      float gv = -coef * p;
+      if (i == tok) gv += coef;
+      out[i] = gv;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- launchers
+static int g_waves_per_row = 4;
+void set_waves_per_row(int w) { g_waves_per_row = (w == 1 || w == 2 || w == 4 || w == 8) ? w : 4; }
+int get_waves_per_row() { return g_waves_per_row; }
+
+template <typename T>
+static void launch_row_stats_t(const RowStatsArgs &a, int blocks, hipStream_t st) {
+  switch (g_waves_per_row) {
+    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, 4>), dim3(blocks), dim3(64), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, 4>), dim3(blocks), dim3(128), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, 4>), dim3(blocks), dim3(512), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_row_stats<T, 4, 4>), dim3(blocks), dim3(256), 0, st, a); break;
+  }
+}
+
+void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st) {
+  if (dtype == 0) launch_row_stats_t<uint16_t>(a, blocks, st);
+  else launch_row_stats_t<float>(a, blocks, st);
+}
+
+void launch_ppo_bwd(const PpoBwdArgs &a, int dtype, int blocks, hipStream_t st) {
+  const bool vec = (a.V % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.grad_rows) & 15) == 0);
+  if (dtype == 0) {
+    if (vec) hipLaunchKernelGGL((k_ppo_bwd<uint16_t, true>), dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_ppo_bwd<uint16_t, false>), dim3(blocks), dim3(256), 0, st, a);
+  } else {
+    if (vec) hipLaunchKernelGGL((k_ppo_bwd<float, true>), dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_ppo_bwd<float, false>), dim3(blocks), dim3(256), 0, st, a);
+  }
+}
+
+}  // namespace gto

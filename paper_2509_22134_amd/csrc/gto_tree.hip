@@ -1,0 +1,372 @@
+// Per-root kernels of the GTO hot path: layer-wise expansion, global re-rank, reward scan and
+// greedy verification walk, group advantage, clipped surrogate forward.  All of them work on a
+// few KB per root that live in LDS; they are latency-bound and tiny next to the row kernels.
+//
+// Ranking everywhere is "rank = number of keys that beat mine" on a packed 64-bit key
+// (order-preserving bits of the fp32 score, then inverted index), which is branch-free,
+// deterministic and realises (score descending, index ascending) exactly.
+#include "gto_device.h"
+#include "gto_kernels.h"
+
+namespace gto {
+
+constexpr int kTreeThreads = 256;
+constexpr int kMaxLevelCands = 4096;  // k^2 for k <= 64
+constexpr int kMaxPool = 4096;        // C
+
+__device__ __forceinline__ uint64_t rank_key(float score, int index) {
+  return ((uint64_t)ordered_bits(score) << 32) | (uint32_t)(0xffffffffu - (uint32_t)index);
+}
+
+// ------------------------------------------------------------------------------ expansion
+__global__ __launch_bounds__(kTreeThreads) void k_expand(ExpandArgs a) {
+  const int r = blockIdx.x;
+  const int k = a.k, d = a.d, kk = a.k * a.k;
+  const int tid = threadIdx.x;
+  __shared__ uint64_t s_key[kMaxLevelCands];
+  __shared__ float s_score[2][64];
+  __shared__ int s_cand[2][64];
+  const int64_t pool0 = (int64_t)r * a.C;
+  const int64_t slot0 = (int64_t)r * d * k;
+
+  // level 0: the root's k children, all expanded at level 1 in rank order
+  for (int t = tid; t < k; t += kTreeThreads) {
+    const int64_t si = stat_index(r, 0, 0, d, k) * k + t;
+    const float sc = __fadd_rn(0.f, a.top_logp[si]);
+    a.cand_tok[pool0 + t] = a.top_tok[si];
+    a.cand_parent[pool0 + t] = -1;
+    a.cand_depth[pool0 + t] = 1;
+    a.cand_pslot[pool0 + t] = 0;
+    a.cand_score[pool0 + t] = sc;
+    a.cand_slot[pool0 + t] = (d > 1) ? t : -1;
+    a.slot_cand[slot0 + t] = -1;
+    if (d > 1) a.slot_cand[slot0 + k + t] = t;
+    s_score[1][t] = sc;
+    s_cand[1][t] = t;
+  }
+  __syncthreads();
+  for (int l = 1; l < d; ++l) {
+    const int cur = l & 1, nxt = cur ^ 1;
+    const int base = k + (l - 1) * kk;
+    for (int t = tid; t < kk; t += kTreeThreads) {
+      const int j = t / k, rk = t - j * k;
+      const int64_t si = stat_index(r, l, j, d, k) * k + rk;
+      const float sc = __fadd_rn(s_score[cur][j], a.top_logp[si]);
+      const int c = base + t;
+      a.cand_tok[pool0 + c] = a.top_tok[si];
+      a.cand_parent[pool0 + c] = s_cand[cur][j];
+      a.cand_depth[pool0 + c] = l + 1;
+      a.cand_pslot[pool0 + c] = j;
+      a.cand_score[pool0 + c] = sc;
+      s_key[t] = rank_key(sc, t);
+      if (l == d - 1) a.cand_slot[pool0 + c] = -1;
+    }
+    if (l == d - 1) break;
+    __syncthreads();
+    for (int t = tid; t < kk; t += kTreeThreads) {
+      const uint64_t mine = s_key[t];
+      int rank = 0;
+      for (int u = 0; u < kk; ++u) rank += (s_key[u] > mine) ? 1 : 0;
+      const int c = base + t;
+      if (rank < k) {
+        s_score[nxt][rank] = a.cand_score[pool0 + c];
+        s_cand[nxt][rank] = c;
+        a.slot_cand[slot0 + (int64_t)(l + 1) * k + rank] = c;
+        a.cand_slot[pool0 + c] = rank;
+      } else {
+        a.cand_slot[pool0 + c] = -1;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+void launch_expand(const ExpandArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_expand, dim3(a.R), dim3(kTreeThreads), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------ top-g
+__global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int C = a.C, g = a.g;
+  const int n_keep = (g < C) ? g : C;
+  __shared__ uint64_t s_key[kMaxPool];
+  __shared__ int s_rank[kMaxPool];
+  __shared__ unsigned char s_leaf[kMaxPool];
+  const int64_t pool0 = (int64_t)r * C;
+  const int64_t sel0 = (int64_t)r * g;
+  for (int c = tid; c < C; c += kTreeThreads) s_key[c] = rank_key(a.cand_score[pool0 + c], c);
+  for (int i = tid; i < n_keep; i += kTreeThreads) s_leaf[i] = 1;
+  __syncthreads();
+  for (int c = tid; c < C; c += kTreeThreads) {
+    const uint64_t mine = s_key[c];
+    int rank = 0;
+    for (int u = 0; u < C; ++u) rank += (s_key[u] > mine) ? 1 : 0;
+    s_rank[c] = rank;
+  }
+  __syncthreads();
+  for (int c = tid; c < C; c += kTreeThreads) {
+    const int p = a.cand_parent[pool0 + c];
+    if (s_rank[c] < n_keep && p >= 0) {
+      const int pr = s_rank[p];
+      if (pr < n_keep) s_leaf[pr] = 0;  // a kept child: the parent is not a leaf
+    }
+  }
+  __syncthreads();
+  for (int c = tid; c < C; c += kTreeThreads) {
+    const int i = s_rank[c];
+    if (i < n_keep) {
+      const int p = a.cand_parent[pool0 + c];
+      a.sel_cand[sel0 + i] = c;
+      a.sel_tok[sel0 + i] = a.cand_tok[pool0 + c];
+      a.sel_parent[sel0 + i] = (p >= 0) ? s_rank[p] : -1;
+      a.sel_depth[sel0 + i] = a.cand_depth[pool0 + c];
+      a.sel_pslot[sel0 + i] = a.cand_pslot[pool0 + c];
+      a.sel_slot[sel0 + i] = a.cand_slot[pool0 + c];
+      a.sel_score[sel0 + i] = a.cand_score[pool0 + c];
+      a.sel_leaf[sel0 + i] = s_leaf[i];
+    }
+  }
+  for (int i = n_keep + tid; i < g; i += kTreeThreads) {
+    a.sel_cand[sel0 + i] = -1;
+    a.sel_tok[sel0 + i] = -1;
+    a.sel_parent[sel0 + i] = -1;
+    a.sel_depth[sel0 + i] = 0;
+    a.sel_pslot[sel0 + i] = 0;
+    a.sel_slot[sel0 + i] = -1;
+    a.sel_score[sel0 + i] = 0.f;
+    a.sel_leaf[sel0 + i] = 0;
+  }
+  if (tid == 0) a.n_sel[r] = n_keep;
+}
+
+void launch_select(const SelectArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_select, dim3(a.R), dim3(kTreeThreads), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------ reward
+constexpr int kRewardThreads = 128;
+constexpr int kMaxDepth = 32;
+
+__device__ __forceinline__ double block_reduce(double v, double *scratch, bool is_max) {
+  const int tid = threadIdx.x;
+  scratch[tid] = v;
+  __syncthreads();
+  for (int off = kRewardThreads / 2; off >= 1; off >>= 1) {
+    if (tid < off) {
+      const double o = scratch[tid + off];
+      scratch[tid] = is_max ? fmax(scratch[tid], o) : scratch[tid] + o;
+    }
+    __syncthreads();
+  }
+  const double out = scratch[0];
+  __syncthreads();
+  return out;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int d = a.d, k = a.k, g = a.g;
+  const int n = a.n_sel[r];
+  const int64_t sel0 = (int64_t)r * g;
+  __shared__ double s_logt[kMaxPool];
+  __shared__ int s_parent[kMaxPool];
+  __shared__ double s_red[kRewardThreads];
+  __shared__ int s_found;
+  const T *logits = static_cast<const T *>(a.target_logits);
+
+  // target log-probability of every kept token (one gather each)
+  for (int i = tid; i < n; i += kRewardThreads) {
+    const int lvl = a.sel_depth[sel0 + i] - 1;
+    const int js = a.sel_pslot[sel0 + i];
+    const int tok = a.sel_tok[sel0 + i];
+    const int64_t si = stat_index(r, lvl, js, d, k);
+    const float x = Elem<T>::load1(logits + si * a.row_stride + tok);
+    s_logt[i] = (double)x - (double)a.t_lse[si];
+    s_parent[i] = a.sel_parent[sel0 + i];
+  }
+  __syncthreads();
+
+  // prefix products along each node's own ancestor chain (root first), Eq. 3-4
+  double v_max = -1.0, v_sumL = 0.0, v_cnt = 0.0, v_q = 0.0;
+  double myL[ (kMaxPool + kRewardThreads - 1) / kRewardThreads ];
+  int nmine = 0;
+  for (int i = tid; i < n; i += kRewardThreads) {
+    int chain[kMaxDepth];
+    int len = 0;
+    for (int p = i; p >= 0 && len < kMaxDepth; p = s_parent[p]) chain[len++] = p;
+    double lq = 0.0, cum = 0.0, q = 0.0;
+    for (int s = len - 1; s >= 0; --s) {
+      lq += s_logt[chain[s]];
+      q = exp(lq);
+      cum += q;
+    }
+    a.node_q[sel0 + i] = (float)q;
+    a.node_cum[sel0 + i] = (float)cum;
+    v_q += q;
+    const bool leaf = a.sel_leaf[sel0 + i] != 0;
+    if (leaf) {
+      v_max = fmax(v_max, cum);
+      v_sumL += cum;
+      v_cnt += 1.0;
+    }
+    myL[nmine++] = leaf ? cum : -1.0;
+  }
+  for (int i = n + tid; i < g; i += kRewardThreads) {
+    a.node_q[sel0 + i] = 0.f;
+    a.node_cum[sel0 + i] = 0.f;
+  }
+  const double Lmax = block_reduce(v_max, s_red, true);
+  double v_exp = 0.0;
+  for (int q = 0; q < nmine; ++q)
+    if (myL[q] >= 0.0) v_exp += exp((double)a.eta * (myL[q] - Lmax));
+  const double sum_exp = block_reduce(v_exp, s_red, false);
+  const double sumL = block_reduce(v_sumL, s_red, false);
+  const double cnt = block_reduce(v_cnt, s_red, false);
+  const double nodesum = block_reduce(v_q, s_red, false);
+  if (tid == 0) {
+    const double lse = (cnt > 0.0) ? Lmax + log(sum_exp) / (double)a.eta : 0.0;
+    const double mx = (cnt > 0.0) ? Lmax : 0.0;
+    const double mean = (cnt > 0.0) ? sumL / cnt : 0.0;
+    float *aux = a.reward_aux + (int64_t)r * 4;
+    aux[0] = (float)lse;
+    aux[1] = (float)mx;
+    aux[2] = (float)mean;
+    aux[3] = (float)nodesum;
+    const double pick = (a.reward_mode == 0) ? lse : (a.reward_mode == 1) ? mx : (a.reward_mode == 2) ? mean : nodesum;
+    a.reward[r] = (float)pick;
+    a.n_leaves[r] = (int)cnt;
+  }
+
+  // greedy verification walk (T = 0): follow the kept child that equals the target argmax
+  int cur = -1, slot = 0, len = 0;
+  bool alive = true;
+  for (int t = 0; t < d; ++t) {
+    if (tid == 0) s_found = -1;
+    __syncthreads();
+    if (alive) {
+      const int want = a.t_argmax[stat_index(r, t, slot, d, k)];
+      for (int i = tid; i < n; i += kRewardThreads)
+        if (s_parent[i] == cur && a.sel_depth[sel0 + i] == t + 1 && a.sel_tok[sel0 + i] == want) s_found = i;
+    }
+    __syncthreads();
+    const int nxt = alive ? s_found : -1;
+    __syncthreads();
+    if (nxt >= 0) {
+      if (tid == 0) {
+        a.path_node[(int64_t)r * d + t] = nxt;
+        a.path_slot[(int64_t)r * d + t] = slot;
+      }
+      len = t + 1;
+      const int own = a.sel_slot[sel0 + nxt];
+      if (own < 0) alive = false;
+      cur = nxt;
+      slot = own;
+    } else {
+      alive = false;
+      if (tid == 0) {
+        a.path_node[(int64_t)r * d + t] = -1;
+        a.path_slot[(int64_t)r * d + t] = -1;
+      }
+    }
+  }
+  if (tid == 0) a.path_len[r] = len;
+}
+
+void launch_reward(const RewardArgs &a, hipStream_t st) {
+  if (a.dtype == 0) hipLaunchKernelGGL(k_reward<uint16_t>, dim3(a.R), dim3(kRewardThreads), 0, st, a);
+  else hipLaunchKernelGGL(k_reward<float>, dim3(a.R), dim3(kRewardThreads), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------ advantage
+__global__ void k_advantage(AdvArgs a) {
+  const int grp = blockIdx.x * blockDim.x + threadIdx.x;
+  if (grp >= a.R / a.m) return;
+  const int i0 = grp * a.m;
+  double sum = 0.0;
+  for (int i = 0; i < a.m; ++i)
+    sum += (double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0);
+  const double mean = sum / a.m;
+  double var = 0.0;
+  for (int i = 0; i < a.m; ++i) {
+    const double dv = ((double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0)) - mean;
+    var += dv * dv;
+  }
+  const double sd = sqrt(var / a.m);
+  for (int i = 0; i < a.m; ++i) {
+    const double dv = ((double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0)) - mean;
+    a.adv[i0 + i] = (float)(dv / (sd + (double)a.delta));
+  }
+}
+
+void launch_advantage(const AdvArgs &a, hipStream_t st) {
+  const int groups = a.R / a.m;
+  hipLaunchKernelGGL(k_advantage, dim3((groups + 63) / 64), dim3(64), 0, st, a);
+}
+
+// ------------------------------------------------------------------------------ surrogate fwd
+template <typename T>
+__global__ void k_ppo_root(PpoFwdArgs a) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= a.R) return;
+  const int d = a.d, k = a.k;
+  const int l = a.path_len[r];
+  const T *dl = static_cast<const T *>(a.draft_logits);
+  const T *rl = static_cast<const T *>(a.ref_logits);
+  double lm = 0.0, lm0 = 0.0;
+  for (int t = 0; t < l; ++t) {
+    const int64_t rt = (int64_t)r * d + t;
+    const int j = a.path_slot[rt];
+    const int tok = a.sel_tok[(int64_t)r * a.g + a.path_node[rt]];
+    const int64_t si = stat_index(r, t, j, d, k);
+    lm += (double)Elem<T>::load1(dl + si * a.row_stride + tok) - (double)a.draft_lse[si];
+    const double rlse = a.ref_lse_by_step ? (double)a.ref_lse[rt] : (double)a.ref_lse[si];
+    lm0 += (double)Elem<T>::load1(rl + si * a.row_stride + tok) - rlse;
+  }
+  const int lden = (l > 1) ? l : 1;
+  const double s = exp((lm - lm0) / lden);
+  const double A = (double)a.adv[r];
+  const double lo = 1.0 - (double)a.eps, hi = 1.0 + (double)a.eps;
+  const double clipped = fmax(lo, fmin(s, hi));
+  const double term = fmin(s * A, clipped * A);
+  const bool passes = (A >= 0.0) ? (s <= hi) : (s >= lo);
+  const int active = (l > 0 && passes) ? 1 : 0;
+  const int K = a.R / a.m;
+  a.logM[r] = (float)lm;
+  a.logM0[r] = (float)lm0;
+  a.ratio[r] = (float)s;
+  a.term[r] = (float)term;
+  a.active[r] = active;
+  a.coef[r] = (float)((double)a.grad_scale * (-A / ((double)a.m * K)) * active * s / lden);
+}
+
+__global__ __launch_bounds__(256) void k_ppo_loss(PpoFwdArgs a) {
+  // single block: group losses, then their mean with a fixed-shape tree reduction
+  const int K = a.R / a.m;
+  __shared__ double s_red[256];
+  double part = 0.0;
+  for (int grp = threadIdx.x; grp < K; grp += 256) {
+    double sum = 0.0;
+    for (int i = 0; i < a.m; ++i) sum += (double)a.term[grp * a.m + i];
+    const double lg = -sum / a.m;
+    a.loss_group[grp] = (float)lg;
+    part += lg;
+  }
+  s_red[threadIdx.x] = part;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a.loss[0] = (float)(s_red[0] / K);
+}
+
+void launch_ppo_fwd(const PpoFwdArgs &a, hipStream_t st) {
+  const int blocks = (a.R + 63) / 64;
+  if (a.dtype == 0) hipLaunchKernelGGL(k_ppo_root<uint16_t>, dim3(blocks), dim3(64), 0, st, a);
+  else hipLaunchKernelGGL(k_ppo_root<float>, dim3(blocks), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(k_ppo_loss, dim3(1), dim3(256), 0, st, a);
+}
+
+}  // namespace gto

@@ -1,0 +1,60 @@
+"""Orchestration of one pass of the GTO hot path over a batch of roots.
+
+Buffers are allocated once (torch = device memory only); `step` issues the C-ABI calls in
+the order of Algorithm 1 (build both trees, rewards, debias + standardise, surrogate forward,
+gradient w.r.t. the current draft logits) on the current stream and returns without
+synchronising.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import torch
+
+from . import binding as B
+
+
+class GtoPath:
+    def __init__(self, *, R, d, k, g, V, dtype, group_size, device, row_stride=None, eta=1.0, eps=0.2,
+                 delta=1e-6, grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, full_path=True,
+                 want_grad=True):
+        self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=dtype, row_stride=row_stride,
+                                 group_size=group_size, reward_mode=reward_mode, eta=eta, eps=eps,
+                                 delta=delta, grad_scale=grad_scale, flags=flags)
+        self.device = device
+        self.full_path = full_path
+        self.want_grad = want_grad and full_path
+        tags = ("cur", "ref") if full_path else ("cur",)
+        self.buf: Dict[str, Dict[str, Dict[str, torch.Tensor]]] = {}
+        for tag in tags:
+            self.buf[tag] = dict(dstats=B.alloc_draft_stats(self.cfg, device), pool=B.alloc_pool(self.cfg, device),
+                                 tree=B.alloc_tree(self.cfg, device), tstats=B.alloc_target_stats(self.cfg, device),
+                                 reward=B.alloc_reward(self.cfg, device))
+        if full_path:
+            self.adv = torch.empty((R,), dtype=torch.float32, device=device)
+            self.ppo = B.alloc_ppo(self.cfg, device)
+            self.workspace = torch.empty((B.gto_workspace_bytes(self.cfg),), dtype=torch.uint8, device=device)
+        if self.want_grad:
+            self.grad_rows = torch.empty((R, d, V), dtype=torch.float32, device=device)
+            self.grad_slot = torch.empty((R, d), dtype=torch.int32, device=device)
+
+    def build_and_score(self, tag: str, D: torch.Tensor, T: torch.Tensor):
+        b = self.buf[tag]
+        B.gto_expand_tree(self.cfg, D, b["dstats"], b["pool"])
+        B.gto_select_topg(self.cfg, b["pool"], b["tree"])
+        B.gto_tree_reward(self.cfg, b["tree"], T, b["tstats"], b["reward"])
+
+    def step(self, D_cur, T_cur, D_ref: Optional[torch.Tensor] = None, T_ref: Optional[torch.Tensor] = None,
+             ref_stats_known: bool = True):
+        self.build_and_score("cur", D_cur, T_cur)
+        if not self.full_path:
+            return
+        self.build_and_score("ref", D_ref, T_ref)
+        cur, ref = self.buf["cur"], self.buf["ref"]
+        B.gto_group_advantage(self.cfg, cur["reward"]["reward"], ref["reward"]["reward"], self.adv)
+        B.gto_ppo_surrogate_fwd(self.cfg, cur["tree"], cur["reward"], D_cur, cur["dstats"], D_ref,
+                                ref["dstats"] if ref_stats_known else None, self.adv, self.ppo,
+                                workspace=self.workspace)
+        if self.want_grad:
+            B.gto_ppo_surrogate_bwd(self.cfg, cur["tree"], cur["reward"], self.ppo, D_cur, cur["dstats"],
+                                    self.grad_rows, self.grad_slot)

@@ -1,0 +1,348 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Staged protocol
+  stage 1  row kernels vs oracle: token ids, max, argmax bit-exact; lse / logp within tolerance.
+  stage 2  the oracle's tree logic fed the GPU's own fp32 row statistics must reproduce every
+           id, parent, slot, path index and fp32 score bit for bit (both sides then take each
+           ranking decision in the same precision, the kernel's).
+  stage 3  end to end vs the pure fp64 oracle: roots whose smallest fp64 ranking gap is above
+           TAU must match exactly; roots below it are near ties (several results correct) and
+           are covered by stage 2 only.  Floats within 1e-5 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gto_synth as S
+import gpu_util as U
+import paper_2509_22134_amd as G
+from oracle import gto_oracle as O
+from paper_2509_22134_amd.pipeline import GtoPath
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run_full(w, tens, device, row_stride=None, V=None, ref_stats_known=True, flags=0, reward_mode=0,
+              grad_scale=0.5):
+    V = V or w.V
+    path = GtoPath(R=tens["D_cur"].shape[0], d=w.d, k=w.k, g=w.g, V=V, dtype=w.torch_dtype, group_size=w.m,
+                   device=device, row_stride=row_stride, eta=w.eta, eps=w.eps, delta=w.delta,
+                   grad_scale=grad_scale, flags=flags, reward_mode=reward_mode, full_path=w.full_path)
+    if flags == 0 and w.full_path:
+        path.grad_rows.fill_(7.0)       # untouched rows must stay untouched
+    path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"), ref_stats_known=ref_stats_known)
+    torch.cuda.synchronize()
+    return path
+
+
+def _compare_all(w, tens, path, V=None, roots=None, grad_scale=0.5, reward_key="reward_lse", flags=0):
+    """Stages 1-3 for the roots in `roots` (default all)."""
+    V = V or w.V
+    R = tens["D_cur"].shape[0]
+    roots = list(range(R)) if roots is None else list(roots)
+    sub = {n: U.logits_np(t[roots])[..., :V] for n, t in tens.items()}
+    ora = O.full_path(sub["D_cur"], sub["T_cur"], sub.get("D_ref", sub["D_cur"]), sub.get("T_ref", sub["T_cur"]),
+                      k=w.k, d=w.d, g=w.g, m=1, eta=w.eta, eps=w.eps, delta=w.delta, want_grad=False)
+    n_ambig = 0
+    for tag in (("cur", "ref") if w.full_path else ("cur",)):
+        b = path.buf[tag]
+        gd = {k: v[roots] for k, v in U.to_np(b["dstats"]).items()}
+        gt = {k: v[roots] for k, v in U.to_np(b["tstats"]).items()}
+        gpool = {k: v[roots] for k, v in U.to_np(b["pool"]).items()}
+        gtree = {k: v[roots] for k, v in U.to_np(b["tree"]).items()}
+        grew = {k: v[roots] for k, v in U.to_np(b["reward"]).items()}
+        o = ora[tag]
+        Dn = sub["D_" + tag] if "D_" + tag in sub else sub["D_cur"]
+        Tn = sub["T_" + tag] if "T_" + tag in sub else sub["T_cur"]
+        U.check_row_stats(gd, o["dstats"], Dn, w.k)                       # stage 1
+        U.check_target_stats(gt, o["tstats"])
+        pool2, tree2, rew2, path2 = U.oracle_from_gpu_stats(gd, gt, Tn, w.d, w.k, w.g, w.eta)
+        U.check_stage2(gpool, gtree, grew, pool2, tree2, rew2, path2)     # stage 2
+        margin = np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"])
+        clear = np.nonzero(margin >= U.TAU)[0]
+        n_ambig += len(roots) - len(clear)
+        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear)  # stage 3
+    return ora, n_ambig
+
+
+def _compare_ppo(w, tens, path, ora_unused=None, grad_scale=0.5, reward_key="reward_lse", flags=0):
+    """Advantage, surrogate and gradient for the whole batch (groups need all roots)."""
+    V = path.cfg.V
+    sub = {n: U.logits_np(t)[..., :V] for n, t in tens.items()}
+    ora = O.full_path(sub["D_cur"], sub["T_cur"], sub["D_ref"], sub["T_ref"], k=w.k, d=w.d, g=w.g, m=w.m,
+                      eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=grad_scale,
+                      reward_mode=reward_key.replace("reward_", ""))
+    cur = path.buf["cur"]
+    g_tree, g_rew = U.to_np(cur["tree"]), U.to_np(cur["reward"])
+    same_tree = all(np.array_equal(g_tree[n], ora["cur"]["tree"][n]) for n in U.INT_TREE) and \
+        all(np.array_equal(g_rew[n], ora["cur"]["path"][n]) for n in U.INT_PATH) and \
+        np.array_equal(U.to_np(path.buf["ref"]["tree"])["sel_cand"], ora["ref"]["tree"]["sel_cand"])
+    # (a) the kernels on the GPU's own inputs: oracle arithmetic fed GPU rewards / trees / stats
+    g_adv = path.adv.cpu().numpy()
+    adv_same_in = O.group_advantage(g_rew["reward"].astype(np.float64),
+                                    U.to_np(path.buf["ref"]["reward"])["reward"].astype(np.float64), w.m, w.delta)
+    np.testing.assert_allclose(g_adv, adv_same_in, rtol=2e-6, atol=1e-6)
+    gd, gr = U.to_np(cur["dstats"]), U.to_np(path.buf["ref"]["dstats"])
+    gpath = {n: g_rew[n] for n in U.INT_PATH}
+    f2 = O.ppo_surrogate_fwd(gpath, g_tree, sub["D_cur"], gd["row_lse"].astype(np.float64), sub["D_ref"],
+                             gr["row_lse"].astype(np.float64), g_adv.astype(np.float64), w.m, w.eps)
+    gp = U.to_np(path.ppo)
+    for n in ("logM", "logM0", "ratio", "term"):
+        np.testing.assert_allclose(gp[n], f2[n], rtol=1e-5, atol=1e-6, err_msg=n)
+    assert np.array_equal(gp["active"], f2["active"])
+    np.testing.assert_allclose(gp["loss_group"], f2["loss_group"], rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(gp["loss"][0], f2["loss"], rtol=1e-5, atol=1e-6)
+    b2 = O.ppo_surrogate_bwd(gpath, g_tree, f2, sub["D_cur"], gd["row_lse"].astype(np.float64),
+                             g_adv.astype(np.float64), w.m, grad_scale)
+    np.testing.assert_allclose(gp["coef"], b2["coef"], rtol=1e-5, atol=1e-12)
+    g_slot = path.grad_slot.cpu().numpy()
+    g_rows = path.grad_rows.cpu().numpy()
+    want_slot = np.where((b2["coef"] != 0)[:, None], b2["grad_slot"], -1)
+    assert np.array_equal(g_slot, want_slot)
+    for r in range(g_rows.shape[0]):
+        for t in range(w.d):
+            if g_slot[r, t] >= 0:
+                ref_row = b2["grad_rows"][r, t]
+                scale = np.abs(ref_row).max()
+                assert np.abs(g_rows[r, t] - ref_row).max() <= 1e-5 * scale + 1e-12, (r, t)
+            elif flags & G.GTO_FLAG_GRAD_ZERO_FILL:
+                assert not g_rows[r, t].any()
+            else:
+                assert (g_rows[r, t] == 7.0).all()
+    # (b) end to end against the pure fp64 oracle, where the trees agree
+    if same_tree:
+        sd = np.array([np.std((ora["cur"]["reward"][reward_key] - ora["ref"]["reward"][reward_key])[i:i + w.m])
+                       for i in range(0, len(g_adv), w.m)]).repeat(w.m)
+        tol = 1e-5 * (1 + np.abs(ora["adv"])) + 4e-6 * (1 + np.abs(ora["adv"])) / (sd + w.delta)
+        assert np.all(np.abs(g_adv - ora["adv"]) <= tol)
+        ok = sd > 0.05           # groups whose spread is far above the fp32 reward rounding
+        np.testing.assert_allclose(gp["ratio"], ora["ppo"]["ratio"], rtol=1e-5)
+        np.testing.assert_allclose(gp["term"][ok], ora["ppo"]["term"][ok], rtol=2e-4, atol=1e-5)
+    return same_tree
+
+
+# ------------------------------------------------------------------------------------ stage 1 sweeps
+@pytest.mark.parametrize("waves", [1, 2, 4, 8])
+@pytest.mark.parametrize("dtype,V,stride", [("bf16", 8192, 8192), ("bf16", 20011, 20016), ("bf16", 1000, 1000),
+                                            ("bf16", 40, 40), ("f32", 1000, 1000), ("f32", 5003, 5004),
+                                            ("f32", 9000, 9000)])
+def test_row_kernels_match_oracle(gpu_device, dtype, V, stride, waves):
+    _say(f"row kernels dtype={dtype} V={V} stride={stride} waves={waves}")
+    G.gto_set_waves_per_row(waves)
+    try:
+        R, d, k = 5, 3, 10
+        w = S.scaled(S.CONFIGS["llama31_8b"], R=R, V=stride, d=d, k=k, g=20, dtype=dtype, n_peaks=8)
+        tens = S.make_logits(w, gpu_device, want=("D_cur", "T_cur"))
+        D, T = tens["D_cur"], tens["T_cur"]
+        D[0, 1, 2, 5:V:7] = float("-inf")                  # zero-probability tokens
+        D[1, 0, 0, :] = 1.5                                # a flat row: pure id tie-break
+        T[1, 1, 1, :] = -2.0
+        T[2, 2, 3, V - 1] = 40.0                           # argmax in the ragged tail
+        D[2, 2, 1, V - 3:V] = 30.0                         # top entries in the ragged tail, tied
+        if stride > V:
+            D[..., V:] = 99.0                              # padding must never be read as data
+            T[..., V:] = 99.0
+        cfg = G.make_config(R=R, d=d, k=k, g=20, V=V, dtype=w.torch_dtype, row_stride=stride)
+        ds = G.gto_draft_row_stats(cfg, D, G.alloc_draft_stats(cfg, gpu_device))
+        ts = G.gto_target_row_stats(cfg, T, G.alloc_target_stats(cfg, gpu_device))
+        torch.cuda.synchronize()
+        Dn, Tn = U.logits_np(D)[..., :V], U.logits_np(T)[..., :V]
+        U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
+        U.check_target_stats(U.to_np(ts), O.target_row_stats(Tn))
+    finally:
+        G.gto_set_waves_per_row(4)
+
+
+def test_rows_with_fewer_than_k_finite_logits(gpu_device):
+    _say("rows with < k finite logits")
+    R, d, k, V = 2, 2, 4, 2048
+    D = torch.full((R, d, k, V), float("-inf"), device=gpu_device, dtype=torch.bfloat16)
+    D[..., 100] = 1.0
+    D[..., 1900] = 0.5
+    cfg = G.make_config(R=R, d=d, k=k, g=5, V=V, dtype=torch.bfloat16)
+    ds = G.gto_draft_row_stats(cfg, D, G.alloc_draft_stats(cfg, gpu_device))
+    torch.cuda.synchronize()
+    Dn = U.logits_np(D)
+    U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
+
+
+# ------------------------------------------------------------------------------------ full path
+def test_tiny_config_full_path(gpu_device):
+    w = S.CONFIGS["tiny"]
+    _say(f"full path config {w.name}")
+    tens = S.make_logits(w, gpu_device)
+    path = _run_full(w, tens, gpu_device)
+    _, n_ambig = _compare_all(w, tens, path)
+    _compare_ppo(w, tens, path)
+    _say(f"  near-tie roots: {n_ambig}")
+
+
+@pytest.mark.parametrize("name,R,V,kw", [
+    ("llama31_8b", 16, 24000, {}),
+    ("llama31_8b", 8, 20011, {"pad": 20016}),
+    ("qwen3_8b", 16, 16384, {}),
+    ("llama31_8b", 16, 12000, {"ref_sigma": None}),          # independent reference model
+    ("tiny", 8, 1000, {"k": 1, "d": 5, "g": 3}),               # k = 1: greedy chain
+    ("tiny", 8, 400, {"g": 500}),                              # g >= C: everything kept
+    ("tiny", 8, 64, {"d": 1, "k": 8, "g": 4}),                 # single level
+    ("vicuna13b", 16, 8000, {"full_path": True}),
+])
+def test_mid_size_full_path(gpu_device, name, R, V, kw):
+    kw = dict(kw)
+    pad = kw.pop("pad", None)
+    w = S.scaled(S.CONFIGS[name], R=R, V=pad or V, **kw)
+    _say(f"full path mid-size {name} R={R} V={V} {kw}")
+    tens = S.make_logits(w, gpu_device)
+    if pad:
+        for t in tens.values():
+            t[..., V:] = 77.0
+    path = _run_full(w, tens, gpu_device, row_stride=pad, V=V)
+    _, n_ambig = _compare_all(w, tens, path, V=V)
+    _compare_ppo(w, tens, path)
+    _say(f"  near-tie roots: {n_ambig}")
+    assert n_ambig <= max(2, R // 4)
+
+
+def test_reference_stats_recomputed_in_workspace_and_zero_fill(gpu_device):
+    _say("ppo fwd without reference stats; zero fill")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=9000)
+    tens = S.make_logits(w, gpu_device)
+    a = _run_full(w, tens, gpu_device)
+    b = _run_full(w, tens, gpu_device, ref_stats_known=False, flags=G.GTO_FLAG_GRAD_ZERO_FILL)
+    for n in ("ratio", "term", "loss", "coef", "logM0"):
+        np.testing.assert_allclose(b.ppo[n].cpu().numpy(), a.ppo[n].cpu().numpy(), rtol=1e-6, atol=1e-7)
+    assert torch.equal(a.grad_slot, b.grad_slot)
+    _compare_ppo(w, tens, b, flags=G.GTO_FLAG_GRAD_ZERO_FILL)
+    valid = (a.grad_slot >= 0)
+    assert torch.equal(a.grad_rows[valid], b.grad_rows[valid])
+    assert not b.grad_rows[~valid].any()
+
+
+@pytest.mark.parametrize("mode,key", [(G.GTO_REWARD_MAX, "reward_max"), (G.GTO_REWARD_MEAN, "reward_mean"),
+                                      (G.GTO_REWARD_NODESUM, "reward_nodesum")])
+def test_reward_modes_and_no_debias(gpu_device, mode, key):
+    _say(f"reward mode {key}")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=6000)
+    tens = S.make_logits(w, gpu_device)
+    path = _run_full(w, tens, gpu_device, reward_mode=mode)
+    idx = ["reward_lse", "reward_max", "reward_mean", "reward_nodesum"].index(key)
+    cur = path.buf["cur"]["reward"]
+    assert torch.equal(cur["reward"], cur["reward_aux"][:, idx])
+    _compare_ppo(w, tens, path, reward_key=key)
+    adv = torch.empty_like(path.adv)
+    G.gto_group_advantage(path.cfg, cur["reward"], None, adv)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(adv.cpu().numpy(), O.group_advantage(cur["reward"].cpu().numpy(), None, w.m, w.delta),
+                               rtol=2e-6, atol=1e-6)
+
+
+def test_bitwise_deterministic(gpu_device):
+    _say("determinism")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=16000)
+    tens = S.make_logits(w, gpu_device)
+    a = _run_full(w, tens, gpu_device)
+    b = _run_full(w, tens, gpu_device)
+    for tag in ("cur", "ref"):
+        for grp in ("dstats", "pool", "tree", "tstats", "reward"):
+            for n, t in a.buf[tag][grp].items():
+                if grp in ("dstats", "tstats"):
+                    m = torch.from_numpy(U.used_mask(16, w.d, w.k)).to(t.device)
+                    assert torch.equal(t[m], b.buf[tag][grp][n][m]), (tag, grp, n)
+                else:
+                    assert torch.equal(t, b.buf[tag][grp][n]), (tag, grp, n)
+    for n, t in a.ppo.items():
+        assert torch.equal(t, b.ppo[n]), n
+    assert torch.equal(a.grad_slot, b.grad_slot)
+    v = a.grad_slot >= 0
+    assert torch.equal(a.grad_rows[v], b.grad_rows[v])
+
+
+# ------------------------------------------------------------------------------------ full-size configs
+def _properties(w, path, tag="cur"):
+    """Invariants that hold at any size (checked on every root of the full-size run)."""
+    b = path.buf[tag]
+    R = path.cfg.R
+    m = torch.from_numpy(U.used_mask(R, w.d, w.k)).to(b["dstats"]["row_lse"].device)
+    ds, tr, rw = b["dstats"], b["tree"], b["reward"]
+    assert bool((ds["row_lse"][m] >= ds["row_max"][m]).all())
+    tt = ds["top_tok"][m]
+    assert bool(((tt >= 0) & (tt < w.V)).all())
+    lp = ds["top_logp"][m]
+    assert bool((lp <= 0).all()) and bool((lp[:, :-1] >= lp[:, 1:]).all())
+    assert bool((tr["n_sel"] == min(w.g, w.C)).all())
+    assert bool((tr["sel_score"][:, :-1] >= tr["sel_score"][:, 1:]).all())
+    idx = torch.arange(w.g, device=tr["sel_parent"].device)[None, :]
+    assert bool((tr["sel_parent"] < idx).all())
+    aux = rw["reward_aux"]
+    n_leaves = rw["n_leaves"].float()
+    assert bool((aux[:, 1] <= aux[:, 0] + 1e-5).all())
+    assert bool((aux[:, 0] <= aux[:, 1] + torch.log(n_leaves) / w.eta + 1e-5).all())
+    assert bool((aux[:, 3] <= w.d + 1e-4).all()) and bool((aux[:, 2] <= aux[:, 1] + 1e-6).all())
+    assert bool(((rw["path_len"] >= 0) & (rw["path_len"] <= w.d)).all())
+
+
+@pytest.mark.parametrize("name,sample", [("vicuna13b", 8), ("llama31_8b", 6), ("qwen3_8b", 4)])
+def test_full_size_config_sampled_roots(gpu_device, name, sample):
+    w = S.CONFIGS[name]
+    R = w.chunk_roots or w.R                        # config 4 is processed in 256-root chunks
+    wr = S.scaled(w, R=R)
+    _say(f"full size {name}: R={R} V={w.V} k={w.k} d={w.d} g={w.g}")
+    want = ("D_cur", "T_cur", "D_ref", "T_ref") if w.full_path else ("D_cur", "T_cur")
+    tens = S.make_logits(wr, gpu_device, want=want)
+    _say("  inputs generated")
+    path = _run_full(wr, tens, gpu_device)
+    _say("  GPU path done")
+    _properties(wr, path, "cur")
+    if w.full_path:
+        _properties(wr, path, "ref")
+    rng = np.random.default_rng(1234)
+    roots = sorted(rng.choice(R, size=sample, replace=False).tolist())
+    _, n_ambig = _compare_all(wr, tens, path, roots=roots)
+    _say(f"  sampled roots {roots}: near-tie roots {n_ambig}")
+    if w.full_path:
+        # advantage / surrogate on the GPU's own rewards and trees, every root; gradient on sampled rows
+        cur, ref = path.buf["cur"], path.buf["ref"]
+        g_rew = U.to_np(cur["reward"])
+        g_adv = path.adv.cpu().numpy()
+        np.testing.assert_allclose(g_adv, O.group_advantage(g_rew["reward"].astype(np.float64),
+                                   ref["reward"]["reward"].cpu().numpy().astype(np.float64), w.m, w.delta),
+                                   rtol=2e-6, atol=1e-6)
+        gp = U.to_np(path.ppo)
+        g_tree = U.to_np(cur["tree"])
+        lse_c = cur["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
+        lse_r = ref["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
+        K = R // w.m
+        for r in roots:
+            l = int(g_rew["path_len"][r])
+            lm = lm0 = 0.0
+            for t in range(l):
+                j = int(g_rew["path_slot"][r, t]); tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, t]])
+                lm += float(tens["D_cur"][r, t, j, tok]) - lse_c[r, t, j]
+                lm0 += float(tens["D_ref"][r, t, j, tok]) - lse_r[r, t, j]
+            s = np.exp((lm - lm0) / max(l, 1))
+            assert abs(gp["ratio"][r] - s) <= 1e-5 * s
+            A = float(g_adv[r])
+            term = min(s * A, max(1 - w.eps, min(s, 1 + w.eps)) * A)
+            assert abs(gp["term"][r] - term) <= 1e-5 * abs(term) + 1e-7
+            coef = 0.5 * (-A / (w.m * K)) * int(gp["active"][r]) * s / max(l, 1)
+            assert abs(gp["coef"][r] - coef) <= 1e-5 * abs(coef) + 1e-12
+            for t in range(l):
+                j = int(g_rew["path_slot"][r, t])
+                if gp["coef"][r] == 0:
+                    assert int(path.grad_slot[r, t]) == -1
+                    continue
+                assert int(path.grad_slot[r, t]) == j
+                tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, t]])
+                x = tens["D_cur"][r, t, j].double().cpu().numpy()
+                ref_row = -coef * np.exp(x - lse_c[r, t, j]); ref_row[tok] += coef
+                got = path.grad_rows[r, t].cpu().numpy()
+                assert np.abs(got - ref_row).max() <= 1e-5 * np.abs(ref_row).max() + 1e-12
+        np.testing.assert_allclose(gp["loss_group"], [-gp["term"][i:i + w.m].astype(np.float64).mean()
+                                                      for i in range(0, R, w.m)], rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(gp["loss"][0], gp["loss_group"].astype(np.float64).mean(), rtol=1e-5, atol=1e-7)
+    del tens, path
+    torch.cuda.empty_cache()

@@ -134,21 +134,33 @@ def _ranked(indices, score32):
     return sorted(indices, key=lambda c: (-float(score32[c]), c))
 
 
-def _gap_audit(order, upto, score64, parent, logit, margin):
-    """Smallest fp64 score gap between neighbours among the first `upto`+1 ranked
-    entries.  Two children of one parent with the same logit are an exact tie on
-    any arithmetic (resolved by index on both sides) and are skipped."""
+AUDIT_SAFETY = 2.0
+
+
+def _ulp32(x) -> float:
+    x = abs(float(x))
+    return float(np.spacing(np.float32(x))) if math.isfinite(x) else 0.0
+
+
+def _gap_audit(order, upto, score64, parent, logit, err, margin):
+    """Near-tie audit of one ranking decision.  For each pair of neighbours among the first
+    `upto`+1 ranked entries: fp64 score gap divided by AUDIT_SAFETY times the sum of the two
+    candidates' fp32 error budgets (`err`, see expand_tree).  A ratio below 1 means that an
+    implementation whose row statistics differ from this one by fp32 rounding may rank the pair
+    the other way; both orders are then correct.  Skipped, because every arithmetic resolves them
+    by index alike: two children of one parent with the same logit, and two scores of -inf."""
     n = min(upto + 1, len(order))
     for a, b in zip(order[: n - 1], order[1:n]):
         if parent[a] == parent[b] and logit is not None and logit[a] == logit[b]:
             continue
         ga, gb = score64[a], score64[b]
-        if ga == gb:  # covers -inf == -inf
-            gap = 0.0
-        else:
-            gap = abs(ga - gb)
-        if gap < margin[0]:
-            margin[0] = gap
+        if ga == gb and ga == NEG_INF:
+            continue
+        gap = 0.0 if ga == gb else abs(ga - gb)
+        budget = AUDIT_SAFETY * (err[a] + err[b])
+        ratio = gap / budget if budget > 0 else (np.inf if gap > 0 else 0.0)
+        if ratio < margin[0]:
+            margin[0] = ratio
     return margin
 
 
@@ -164,8 +176,12 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
     (l+1, 0..k-1) in that order; the others stay unexpanded candidates.
 
     The score is an fp32 value: score = fp32(score_parent + logp32).  If
-    `top_logp64` is given the fp64 twin is accumulated too and `min_margin[r]`
-    reports the smallest fp64 gap at any ranking decision of root r (otherwise inf).
+    `top_logp64` is given the fp64 twin is accumulated too, together with an error
+    budget per candidate, err = err(parent) + ulp32(logp) + ulp32(score)/2 (an
+    implementation's fp32 log-probability may be one ulp away from this one's, and
+    each fp32 add rounds by half an ulp); `min_margin[r]` is then the smallest
+    gap-to-budget ratio (see _gap_audit) over the ranking decisions of root r:
+    >= 1 means every decision of that root is clear of fp32 rounding.
 
     Returns dict: cand_tok, cand_parent (pool index or -1), cand_depth (1..d),
     cand_pslot (slot j of the parent within its level), cand_slot (slot the node
@@ -184,6 +200,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
     cand_score = np.zeros((R, C), dtype=np.float32)
     cand_score64 = np.zeros((R, C), dtype=np.float64)
     cand_logit = np.zeros((R, C), dtype=np.float64)
+    cand_err = np.zeros((R, C), dtype=np.float64)
     slot_cand = np.full((R, d, k), -1, dtype=np.int32)
     min_margin = np.full((R,), np.inf)
     lp64 = top_logp64 if top_logp64 is not None else top_logp32.astype(np.float64)
@@ -198,6 +215,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
             cand_pslot[r, c] = 0
             cand_score[r, c] = np.float32(0.0) + np.float32(top_logp32[r, 0, 0, rank])
             cand_score64[r, c] = lp64[r, 0, 0, rank]
+            cand_err[r, c] = _ulp32(top_logp32[r, 0, 0, rank])
             if top_logit is not None:
                 cand_logit[r, c] = top_logit[r, 0, 0, rank]
         if d > 1:
@@ -216,6 +234,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
                     cand_pslot[r, c] = j
                     cand_score[r, c] = np.float32(cand_score[r, p]) + np.float32(top_logp32[r, l, j, rank])
                     cand_score64[r, c] = cand_score64[r, p] + lp64[r, l, j, rank]
+                    cand_err[r, c] = cand_err[r, p] + _ulp32(top_logp32[r, l, j, rank]) + 0.5 * _ulp32(cand_score[r, c])
                     if top_logit is not None:
                         cand_logit[r, c] = top_logit[r, l, j, rank]
             if l < d - 1:
@@ -225,11 +244,11 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
                     cand_slot[r, order[i]] = i
                 if top_logp64 is not None:
                     _gap_audit(order, k, cand_score64[r], cand_parent[r],
-                               cand_logit[r] if top_logit is not None else None, margin)
+                               cand_logit[r] if top_logit is not None else None, cand_err[r], margin)
         min_margin[r] = margin[0]
     return dict(cand_tok=cand_tok, cand_parent=cand_parent, cand_depth=cand_depth,
                 cand_pslot=cand_pslot, cand_slot=cand_slot, cand_score=cand_score,
-                cand_score64=cand_score64, cand_logit=cand_logit, slot_cand=slot_cand,
+                cand_score64=cand_score64, cand_logit=cand_logit, cand_err=cand_err, slot_cand=slot_cand,
                 min_margin=min_margin)
 
 
@@ -245,8 +264,8 @@ def select_topg(pool, g: int, audit: bool = False):
     Returns dict (all [R, g], unused tail = -1 / 0): sel_cand (pool index),
     sel_tok, sel_parent (position of the parent in the kept list, -1 for depth-1
     nodes), sel_depth, sel_pslot, sel_slot, sel_leaf (1 if no kept child),
-    sel_score fp32; n_sel [R]; min_margin [R] (fp64 gap audit over the kept
-    order and the cut, only if audit=True).
+    sel_score fp32; n_sel [R]; min_margin [R] (near-tie audit over the kept
+    order and the cut, only if audit=True; see _gap_audit).
     """
     cand_score = pool["cand_score"]
     R, C = cand_score.shape
@@ -282,7 +301,7 @@ def select_topg(pool, g: int, audit: bool = False):
         if audit:
             margin = [np.inf]
             _gap_audit(order, n_keep, pool["cand_score64"][r], pool["cand_parent"][r],
-                       pool.get("cand_logit", [None] * R)[r], margin)
+                       pool.get("cand_logit", [None] * R)[r], pool["cand_err"][r], margin)
             min_margin[r] = margin[0]
     out = dict(sel)
     out.update(sel_leaf=sel_leaf, sel_score=sel_score, n_sel=n_sel, min_margin=min_margin)

@@ -108,7 +108,8 @@ def make_config(*, R, d, k, g, V, dtype, row_stride=None, group_size=1, reward_m
 
 # ------------------------------------------------------------------ output containers (torch = memory only)
 def _alloc(spec, device):
-    return {n: torch.empty(shape, dtype=dt, device=device) for n, (shape, dt) in spec.items()}
+    # zero-filled so that entries the kernels never write (padding slots of level 0) are defined
+    return {n: torch.zeros(shape, dtype=dt, device=device) for n, (shape, dt) in spec.items()}
 
 
 def alloc_draft_stats(cfg, device) -> Dict[str, torch.Tensor]:

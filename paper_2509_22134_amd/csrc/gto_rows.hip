@@ -44,10 +44,13 @@ __device__ __forceinline__ float kth_largest_of_lanes(float x, int k) {
 }
 
 // Per-lane streaming state: running max m, log2-domain offset c = m*log2(e) and
-// s = sum 2^(x*log2(e) - c) over the elements this lane has seen.
+// s = sum 2^(x*log2(e) - c) over the elements this lane has seen.  Each 16-byte vector is summed
+// in fp32 and then added to s in fp64 (a full-rate add on this chip): an fp32 running sum that
+// already holds a dominant term would silently drop the many tiny ones added after it.
 struct LaneAcc {
-  float m, c, s;
-  __device__ __forceinline__ void init() { m = neg_inf(); c = 0.f; s = 0.f; }
+  float m, c;
+  double s;
+  __device__ __forceinline__ void init() { m = neg_inf(); c = 0.f; s = 0.0; }
 };
 
 template <typename T, int LOADS, bool GUARD>
@@ -86,11 +89,14 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
   const float m_new = fmaxf(acc.m, cm);
   const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
   const float scale = __builtin_amdgcn_exp2f(acc.c - c_new);
-  float s = (acc.m == neg_inf()) ? 0.f : acc.s * scale;
+  double s = (acc.m == neg_inf()) ? 0.0 : acc.s * (double)scale;
 #pragma unroll
-  for (int u = 0; u < LOADS; ++u)
+  for (int u = 0; u < LOADS; ++u) {
+    float p = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPV; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][e], kLog2e, -c_new));
+    for (int e = 0; e < EPV; ++e) p += __builtin_amdgcn_exp2f(__builtin_fmaf(x[u][e], kLog2e, -c_new));
+    s += (double)p;
+  }
   acc.m = m_new;
   acc.c = c_new;
   acc.s = s;
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
   const float Mw = wave_max(acc.m);
   const float Cw = wave_max(acc.m == neg_inf() ? neg_inf() : acc.c);
   const double contrib =
-      (acc.m == neg_inf()) ? 0.0 : (double)acc.s * (double)__builtin_amdgcn_exp2f(acc.c - Cw);
+      (acc.m == neg_inf()) ? 0.0 : acc.s * (double)__builtin_amdgcn_exp2f(acc.c - Cw);
   const double Sw = wave_sum(contrib);
 
   __shared__ float sh_v[WAVES * kWave];

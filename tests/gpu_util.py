@@ -4,7 +4,7 @@ import torch
 
 from oracle import gto_oracle as O
 
-TAU = 2e-5          # fp64 score gap below which a ranking decision counts as a near tie
+TAU = 1.0           # oracle's gap-to-error-budget ratio below which a ranking decision is a near tie
 
 
 def to_np(d):
@@ -60,14 +60,24 @@ def oracle_from_gpu_stats(gd, gt, T_np, d, k, g, eta):
     return pool, tree, rew, path
 
 
-def check_stage2(gpool, gtree, grew, opool, otree, orew, opath, roots=None):
+def _scores_equal(a, b, exact):
+    if exact:
+        return np.array_equal(a, b)
+    fin = np.isfinite(b)
+    return np.array_equal(np.isfinite(a), fin) and \
+        np.all(np.abs(a[fin].astype(np.float64) - b[fin]) <= 1e-6 * np.abs(b[fin]) + 4e-6)
+
+
+def check_stage2(gpool, gtree, grew, opool, otree, orew, opath, roots=None, exact_scores=True):
+    """Every integer output bit-exact.  Scores: bit-exact when both sides started from the same fp32
+    row statistics (stage 2); within a few fp32 roundings against the pure fp64 oracle (stage 3)."""
     sl = slice(None) if roots is None else roots
     for name in INT_POOL:
         assert np.array_equal(gpool[name][sl], opool[name][sl]), name
-    assert np.array_equal(gpool["cand_score"][sl], opool["cand_score"][sl]), "cand_score"
+    assert _scores_equal(gpool["cand_score"][sl], opool["cand_score"][sl], exact_scores), "cand_score"
     for name in INT_TREE:
         assert np.array_equal(gtree[name][sl], otree[name][sl]), name
-    assert np.array_equal(gtree["sel_score"][sl], otree["sel_score"][sl]), "sel_score"
+    assert _scores_equal(gtree["sel_score"][sl], otree["sel_score"][sl], exact_scores), "sel_score"
     for name in INT_PATH:
         assert np.array_equal(grew[name][sl], opath[name][sl]), name
     assert np.array_equal(grew["n_leaves"][sl], orew["n_leaves"][sl])

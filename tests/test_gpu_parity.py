@@ -65,7 +65,8 @@ def _compare_all(w, tens, path, V=None, roots=None, grad_scale=0.5, reward_key="
         margin = np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"])
         clear = np.nonzero(margin >= U.TAU)[0]
         n_ambig += len(roots) - len(clear)
-        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear)  # stage 3
+        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear,
+                       exact_scores=False)                                # stage 3
     return ora, n_ambig
 
 

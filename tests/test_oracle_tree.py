@@ -160,13 +160,20 @@ def test_margin_audit_flags_near_ties_only():
     D[0, 1, 0, 2], D[0, 1, 0, 3] = 3.0, 1.0
     D[0, 1, 1, 4], D[0, 1, 1, 5] = 3.0, 0.5
     _, pool, tree = _build(D, k, d, 3)
-    assert tree["min_margin"][0] > 1e-2
-    # move the first pruned candidate to within 1e-9 of the last kept one
-    st = O.draft_row_stats(D, k)
-    pool = O.expand_tree(st["top_tok"], st["top_logp32"], d, k, st["top_logp64"], st["top_logit"])
+    assert tree["min_margin"][0] > 1e3 and pool["min_margin"][0] == np.inf   # clear by a wide margin
+    # move the first pruned candidate to within 1e-9 of the last kept one: now a near tie
     order = sorted(range(6), key=lambda c: (-pool["cand_score64"][0, c], c))
     gap = pool["cand_score64"][0, order[2]] - pool["cand_score64"][0, order[3]]
     assert gap > 0
     pool["cand_score64"][0, order[3]] += gap - 1e-9
-    tree2 = O.select_topg(pool, 3, audit=True)
-    assert tree2["min_margin"][0] < 1e-8
+    assert O.select_topg(pool, 3, audit=True)["min_margin"][0] < 1.0
+    # a gap of a few fp32 ulps of the scores is still flagged, a gap of 1e-4 is not
+    pool["cand_score64"][0, order[3]] -= 1e-7
+    assert O.select_topg(pool, 3, audit=True)["min_margin"][0] < 1.0
+    pool["cand_score64"][0, order[3]] -= 1e-4
+    assert O.select_topg(pool, 3, audit=True)["min_margin"][0] > 1.0
+    # exact ties that every arithmetic resolves by index are not flagged
+    D2 = np.full((1, d, k, V), -np.inf)
+    D2[..., 4] = 0.0
+    _, pool2, tree2 = _build(D2, k, d, 3)
+    assert tree2["min_margin"][0] == np.inf or tree2["min_margin"][0] >= 1.0

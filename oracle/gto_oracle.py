@@ -135,6 +135,7 @@ def _ranked(indices, score32):
 
 
 AUDIT_SAFETY = 2.0
+SUM_REL_ERR = 2.0 ** -23      # relative accuracy granted to an fp32 sum of exponentials
 
 
 def _ulp32(x) -> float:
@@ -148,10 +149,13 @@ def _gap_audit(order, upto, score64, parent, logit, err, margin):
     candidates' fp32 error budgets (`err`, see expand_tree).  A ratio below 1 means that an
     implementation whose row statistics differ from this one by fp32 rounding may rank the pair
     the other way; both orders are then correct.  Skipped, because every arithmetic resolves them
-    by index alike: two children of one parent with the same logit, and two scores of -inf."""
+    alike: two children of one parent with the same logit and two scores of -inf (index order), and
+    a node next to its own parent (a log-probability is <= 0 and the parent's index is lower)."""
     n = min(upto + 1, len(order))
     for a, b in zip(order[: n - 1], order[1:n]):
         if parent[a] == parent[b] and logit is not None and logit[a] == logit[b]:
+            continue
+        if parent[b] == a or parent[a] == b:
             continue
         ga, gb = score64[a], score64[b]
         if ga == gb and ga == NEG_INF:
@@ -177,9 +181,10 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
 
     The score is an fp32 value: score = fp32(score_parent + logp32).  If
     `top_logp64` is given the fp64 twin is accumulated too, together with an error
-    budget per candidate, err = err(parent) + ulp32(logp) + ulp32(score)/2 (an
-    implementation's fp32 log-probability may be one ulp away from this one's, and
-    each fp32 add rounds by half an ulp); `min_margin[r]` is then the smallest
+    budget per candidate, err = err(parent) + ulp32(logp) + 2^-23 + ulp32(score)/2
+    (an implementation's fp32 log-probability may be one ulp away from this one's,
+    its sum of exponentials is only accurate to fp32 relative precision, and each
+    fp32 add rounds by half an ulp); `min_margin[r]` is then the smallest
     gap-to-budget ratio (see _gap_audit) over the ranking decisions of root r:
     >= 1 means every decision of that root is clear of fp32 rounding.
 
@@ -215,7 +220,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
             cand_pslot[r, c] = 0
             cand_score[r, c] = np.float32(0.0) + np.float32(top_logp32[r, 0, 0, rank])
             cand_score64[r, c] = lp64[r, 0, 0, rank]
-            cand_err[r, c] = _ulp32(top_logp32[r, 0, 0, rank])
+            cand_err[r, c] = _ulp32(top_logp32[r, 0, 0, rank]) + SUM_REL_ERR
             if top_logit is not None:
                 cand_logit[r, c] = top_logit[r, 0, 0, rank]
         if d > 1:
@@ -234,7 +239,8 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
                     cand_pslot[r, c] = j
                     cand_score[r, c] = np.float32(cand_score[r, p]) + np.float32(top_logp32[r, l, j, rank])
                     cand_score64[r, c] = cand_score64[r, p] + lp64[r, l, j, rank]
-                    cand_err[r, c] = cand_err[r, p] + _ulp32(top_logp32[r, l, j, rank]) + 0.5 * _ulp32(cand_score[r, c])
+                    cand_err[r, c] = cand_err[r, p] + _ulp32(top_logp32[r, l, j, rank]) + SUM_REL_ERR \
+                        + 0.5 * _ulp32(cand_score[r, c])
                     if top_logit is not None:
                         cand_logit[r, c] = top_logit[r, l, j, rank]
             if l < d - 1:

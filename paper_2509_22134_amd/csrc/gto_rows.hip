@@ -231,7 +231,8 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
       for (int i = 0; i < a.ktop; ++i) rank += better(sh_v[w * kWave + i], sh_i[w * kWave + i], v, id) ? 1 : 0;
     if (rank < a.ktop && id != kNoId) {
       a.top_tok[oi * a.ktop + rank] = id;
-      if (a.top_logp) a.top_logp[oi * a.ktop + rank] = (float)((double)v - sh_lse);
+      // clamped: rounding must never make a log-probability positive (a child may not outrank its parent)
+      if (a.top_logp) a.top_logp[oi * a.ktop + rank] = fminf((float)((double)v - sh_lse), 0.f);
     }
   }
 }
@@ -262,6 +263,10 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
   const int tok = a.sel_tok[(int64_t)r * a.g + a.path_node[rt]];
   const float lse = a.row_lse[stat_index(r, t, j, a.d, a.k)];
   const T *__restrict__ row = static_cast<const T *>(a.logits) + stat_index(r, t, j, a.d, a.k) * a.row_stride;
+  // Every entry but the token's is -coef * p_v.  The token's entry coef * (1 - p_tok) is formed as
+  // coef * (sum of the other probabilities): when p_tok is close to 1 the subtraction would cancel.
+  float others = 0.f;
+  bool own_tok = false;
   if (VEC) {
     // four elements per lane per step: one 8- or 16-byte load, one 16-byte store
     const int n4 = V / 4;
@@ -277,12 +282,16 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
         x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
       }
       float gq[4];
+      float part = 0.f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float p = __builtin_amdgcn_exp2f((x[e] - lse) * kLog2e);
         gq[e] = -coef * p;
-        if (i * 4 + e == tok) gq[e] += coef;
+        const bool is_tok = (i * 4 + e == tok);
+        own_tok = own_tok || is_tok;
+        part += is_tok ? 0.f : p;
       }
+      others += part;
       const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
       __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
     }
@@ -290,11 +299,21 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
     for (int i = threadIdx.x; i < V; i += blockDim.x) {
       const float xv = Elem<T>::load1(row + i);
       const float p = __builtin_amdgcn_exp2f((xv - lse) * kLog2e);
-      float gv = -coef * p;
-      if (i == tok) gv += coef;
-      out[i] = gv;
+      const bool is_tok = (i == tok);
+      own_tok = own_tok || is_tok;
+      others += is_tok ? 0.f : p;
+      out[i] = -coef * p;
     }
   }
+  __shared__ double s_part[256];
+  s_part[threadIdx.x] = (double)others;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) s_part[threadIdx.x] += s_part[threadIdx.x + off];
+    __syncthreads();
+  }
+  // the thread that stored the token's entry overwrites it (same thread, program order)
+  if (own_tok) out[tok] = (float)((double)coef * s_part[0]);
 }
 
 // ------------------------------------------------------------------------------- launchers

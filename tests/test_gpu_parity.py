@@ -97,7 +97,8 @@ def _compare_ppo(w, tens, path, ora_unused=None, grad_scale=0.5, reward_key="rew
     assert np.array_equal(gp["active"], f2["active"])
     np.testing.assert_allclose(gp["loss_group"], f2["loss_group"], rtol=1e-5, atol=1e-6)
     np.testing.assert_allclose(gp["loss"][0], f2["loss"], rtol=1e-5, atol=1e-6)
-    b2 = O.ppo_surrogate_bwd(gpath, g_tree, f2, sub["D_cur"], gd["row_lse"].astype(np.float64),
+    # gradient rows against the oracle's own fp64 softmax (same path, advantage and ratio)
+    b2 = O.ppo_surrogate_bwd(gpath, g_tree, f2, sub["D_cur"], ora["cur"]["dstats"]["row_lse"],
                              g_adv.astype(np.float64), w.m, grad_scale)
     np.testing.assert_allclose(gp["coef"], b2["coef"], rtol=1e-5, atol=1e-12)
     g_slot = path.grad_slot.cpu().numpy()
@@ -339,7 +340,8 @@ def test_full_size_config_sampled_roots(gpu_device, name, sample):
                 assert int(path.grad_slot[r, t]) == j
                 tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, t]])
                 x = tens["D_cur"][r, t, j].double().cpu().numpy()
-                ref_row = -coef * np.exp(x - lse_c[r, t, j]); ref_row[tok] += coef
+                ref_row = -coef * np.exp(x - float(torch.logsumexp(tens["D_cur"][r, t, j].double(), 0)))
+                ref_row[tok] += coef
                 got = path.grad_rows[r, t].cpu().numpy()
                 assert np.abs(got - ref_row).max() <= 1e-5 * np.abs(ref_row).max() + 1e-12
         np.testing.assert_allclose(gp["loss_group"], [-gp["term"][i:i + w.m].astype(np.float64).mean()

@@ -161,19 +161,25 @@ def test_margin_audit_flags_near_ties_only():
     D[0, 1, 1, 4], D[0, 1, 1, 5] = 3.0, 0.5
     _, pool, tree = _build(D, k, d, 3)
     assert tree["min_margin"][0] > 1e3 and pool["min_margin"][0] == np.inf   # clear by a wide margin
-    # move the first pruned candidate to within 1e-9 of the last kept one: now a near tie
+    # move the third-ranked candidate to within 1e-9 of the second (they are not parent and child)
     order = sorted(range(6), key=lambda c: (-pool["cand_score64"][0, c], c))
-    gap = pool["cand_score64"][0, order[2]] - pool["cand_score64"][0, order[3]]
+    hi, lo = order[1], order[2]
+    assert pool["cand_parent"][0, lo] != hi and pool["cand_parent"][0, hi] != lo
+    gap = pool["cand_score64"][0, hi] - pool["cand_score64"][0, lo]
     assert gap > 0
-    pool["cand_score64"][0, order[3]] += gap - 1e-9
+    pool["cand_score64"][0, lo] += gap - 1e-9
     assert O.select_topg(pool, 3, audit=True)["min_margin"][0] < 1.0
-    # a gap of a few fp32 ulps of the scores is still flagged, a gap of 1e-4 is not
-    pool["cand_score64"][0, order[3]] -= 1e-7
+    # a gap of about one fp32 ulp of the scores is still flagged, a gap of 1e-4 is not
+    pool["cand_score64"][0, lo] -= 1e-7
     assert O.select_topg(pool, 3, audit=True)["min_margin"][0] < 1.0
-    pool["cand_score64"][0, order[3]] -= 1e-4
+    pool["cand_score64"][0, lo] -= 1e-4
     assert O.select_topg(pool, 3, audit=True)["min_margin"][0] > 1.0
-    # exact ties that every arithmetic resolves by index are not flagged
-    D2 = np.full((1, d, k, V), -np.inf)
-    D2[..., 4] = 0.0
-    _, pool2, tree2 = _build(D2, k, d, 3)
-    assert tree2["min_margin"][0] == np.inf or tree2["min_margin"][0] >= 1.0
+    # a child within rounding of its own parent is never a near tie: the parent always ranks first
+    child = [c for c in range(6) if pool["cand_parent"][0, c] == order[0]][0]
+    pool["cand_score64"][0, child] = pool["cand_score64"][0, order[0]] - 1e-12
+    assert O.select_topg(pool, 3, audit=True)["min_margin"][0] > 1.0
+    # exact ties that every arithmetic resolves alike (parent/child at logp 0, -inf against -inf)
+    D3 = np.full((1, d, k, V), -np.inf)
+    D3[0, 0, 0, 1], D3[0, 1, 0, 2], D3[0, 1, 1, 3] = 0.0, 0.0, 0.0
+    _, pool3, tree3 = _build(D3, k, d, 5)          # kept: the chain 1 -> 2, then -inf candidates by index
+    assert tree3["sel_cand"][0].tolist() == [0, 2, 1, 3, 4] and tree3["min_margin"][0] == np.inf

@@ -1,0 +1,134 @@
+#!/usr/bin/env python3
+"""Benchmark of the GTO hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic logits already resident
+in HBM: for the current and the frozen-reference draft model, row statistics + top-k of every
+used draft row, layer-wise expansion, global top-g, target row statistics, Draft Tree Reward and
+greedy verification walk; then debiased group-standardised advantages, the clipped surrogate
+and its gradient w.r.t. the current draft logits.
+
+Prints ONE JSON line: trees scored per second (value), plus `roofline` for the dominant kernel
+(the draft row kernel; algorithmic bytes / HIP-event time measured on the launch stream inside
+the timed region) and `cpu_baseline` (the CPU oracle timed on a bounded sample of the same
+workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
+
+
+def cpu_baseline(w, tens, n_roots, torch):
+    """The oracle as it stands, on the first `n_roots` roots of the same tensors."""
+    import numpy as np
+    from oracle import gto_oracle as O
+    host = {n: t[:n_roots].float().cpu().numpy() for n, t in tens.items()}
+    m = w.m if n_roots % w.m == 0 else 1
+    t0 = time.perf_counter()
+    O.full_path(host["D_cur"], host["T_cur"], host["D_ref"], host["T_ref"], k=w.k, d=w.d, g=w.g, m=m,
+                eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5)
+    dt = time.perf_counter() - t0
+    return {"value": 2 * n_roots / dt, "unit": "trees/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n_roots} roots of the workload (2 trees each, full path incl. gradient), "
+                      f"{dt:.1f} s of single-threaded numpy"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama31_8b")
+    ap.add_argument("--roots", type=int, default=0, help="override the number of roots (debug)")
+    ap.add_argument("--waves", type=int, default=0, help="wavefronts per row in the row kernels (tuning)")
+    ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import gto_synth as S
+    import paper_2509_22134_amd as G
+    from paper_2509_22134_amd.pipeline import GtoPath
+
+    if not os.path.exists(G.lib_path()):
+        from paper_2509_22134_amd.build import build_lib
+        build_lib()
+    dev = torch.device("cuda:0")
+    w = S.CONFIGS[args.workload]
+    if args.roots:
+        w = S.scaled(w, R=args.roots)
+    if args.waves:
+        G.gto_set_waves_per_row(args.waves)
+    R = w.chunk_roots or w.R
+    n_chunks = w.R // R
+    wr = S.scaled(w, R=R)
+    want = ("D_cur", "T_cur", "D_ref", "T_ref") if w.full_path else ("D_cur", "T_cur")
+    tens = S.make_logits(wr, dev, want=want)        # one chunk resident; chunks reuse the buffers
+    path = GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=dev,
+                   eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path)
+
+    def step():
+        for _ in range(n_chunks):
+            path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    G.gto_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    G.gto_profile_enable(False)
+    prof = G.gto_profile_read()
+
+    trees_per_step = w.R * (2 if w.full_path else 1)
+    ms_per_step = dt / args.steps * 1e3
+    value = trees_per_step / (dt / args.steps)
+    fwd_bytes = S.algorithmic_bytes(w, 2 if w.full_path else 1)
+    kernels = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in prof.items()}
+    dom = "row_stats_draft"
+    dom_bytes = R * w.rho * w.V * w.elem_bytes          # every used draft row once per launch
+    dom_ms = kernels[dom]["avg_ms"]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        traffic = tj.get(f"{dom}:{w.name}")
+    out = {
+        "metric": "draft trees scored/sec (build+reward+PPO) and achieved HBM GB/s, V=%d" % w.V,
+        "value": value, "unit": "trees/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: R={w.R} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m} "
+                               f"{w.dtype} logits, " + ("full path, current + reference tree per root"
+                                                       if w.full_path else "reward only"),
+                   "chunks": n_chunks, "waves_per_row": G.gto_set_waves_per_row(args.waves or 4)},
+        "logit_gb_s": fwd_bytes / (dt / args.steps) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
+        "kernels": kernels,
+    }
+    if args.cpu_roots > 0 and w.full_path:
+        out["cpu_baseline"] = cpu_baseline(w, tens, min(args.cpu_roots, R), torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

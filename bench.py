@@ -118,7 +118,7 @@ def main():
         "config": {"workload": f"{w.name}: R={w.R} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m} "
                                f"{w.dtype} logits, " + ("full path, current + reference tree per root"
                                                        if w.full_path else "reward only"),
-                   "chunks": n_chunks, "waves_per_row": G.gto_set_waves_per_row(args.waves or 4)},
+                   "chunks": n_chunks, "waves_per_row": args.waves or "auto"},
         "logit_gb_s": fwd_bytes / (dt / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

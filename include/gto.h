@@ -205,8 +205,9 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur,
                           const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
                           float *grad_rows, int32_t *grad_slot, void *hip_stream);
 
-/* Tuning knob: wavefronts that share one logits row in the row kernels (1, 2, 4 or 8; other
- * values select the default 4).  Process-wide; returns the value in effect. */
+/* Tuning knob: wavefronts that share one logits row in the row kernels (1, 2, 4 or 8; any other
+ * value restores the default, a per-launch choice from V and the number of rows).  Process-wide;
+ * returns the value in effect, 0 meaning the per-launch choice. */
 int gto_set_waves_per_row(int waves);
 
 /* Optional per-kernel timing.  While enabled, every kernel launch of the calling thread is

@@ -53,10 +53,13 @@ struct LaneAcc {
   __device__ __forceinline__ void init() { m = neg_inf(); c = 0.f; s = 0.0; }
 };
 
-template <typename T, int LOADS, bool GUARD>
+enum RowMode { kDraftTopK = 0, kTargetArgmax = 1, kLseOnly = 2 };
+
+template <typename T, int LOADS, bool GUARD, int MODE>
 __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_base, int V, int lane,
-                                          int ktop, bool &first, LaneAcc &acc, TopList &top,
+                                          int ktop_rt, bool &first, LaneAcc &acc, TopList &top,
                                           float &thr_v, int &thr_i) {
+  const int ktop = (MODE == kTargetArgmax) ? 1 : ktop_rt;
   constexpr int EPV = Elem<T>::kPerVec;
   float x[LOADS][EPV];
   u32x4 q[LOADS];
@@ -79,11 +82,16 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
         if (e0 + e >= V) x[u][e] = neg_inf();
     }
   }
-  float cm = x[0][0];
+  float mu[LOADS];
 #pragma unroll
-  for (int u = 0; u < LOADS; ++u)
+  for (int u = 0; u < LOADS; ++u) {
+    mu[u] = x[u][0];
 #pragma unroll
-    for (int e = 0; e < EPV; ++e) cm = fmaxf(cm, x[u][e]);
+    for (int e = 1; e < EPV; ++e) mu[u] = fmaxf(mu[u], x[u][e]);
+  }
+  float cm = mu[0];
+#pragma unroll
+  for (int u = 1; u < LOADS; ++u) cm = fmaxf(cm, mu[u]);
 
   // online log-sum-exp in the log2 domain
   const float m_new = fmaxf(acc.m, cm);
@@ -101,6 +109,7 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
   acc.c = c_new;
   acc.s = s;
 
+  if (MODE == kLseOnly) return;
   // top-k: first tile of a wave seeds the threshold with the k-th largest lane maximum, a
   // value that at least k elements of this tile reach.
   if (first) {
@@ -114,6 +123,9 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
 
 #pragma unroll
   for (int u = 0; u < LOADS; ++u) {
+    // skip a whole vector position when no lane's vector maximum can enter the list
+    if (__builtin_amdgcn_ballot_w64(better(mu[u], tile_base + (u * kWave + lane) * EPV, thr_v, thr_i)) == 0)
+      continue;
 #pragma unroll
     for (int e = 0; e < EPV; ++e) {
       const int my_id = tile_base + (u * kWave + lane) * EPV + e;
@@ -139,7 +151,7 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
   }
 }
 
-template <typename T, int WAVES, int LOADS>
+template <typename T, int WAVES, int LOADS, int MODE>
 __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
   constexpr int EPV = Elem<T>::kPerVec;
   constexpr int TILE = kWave * LOADS * EPV;
@@ -175,9 +187,9 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
 
   const int n_full = V / TILE;
   for (int t = wave; t < n_full; t += WAVES)
-    scan_tile<T, LOADS, false>(row, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+    scan_tile<T, LOADS, false, MODE>(row, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
   if (n_full * TILE < V && (n_full % WAVES) == wave)
-    scan_tile<T, LOADS, true>(row, n_full * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+    scan_tile<T, LOADS, true, MODE>(row, n_full * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
 
   // wave-level reduction of (max, offset, sum)
   const float Mw = wave_max(acc.m);
@@ -220,7 +232,7 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
     if (a.row_max) a.row_max[oi] = M;
     a.row_lse[oi] = (float)lse;
   }
-  if (a.top_tok == nullptr) return;
+  if (MODE == kLseOnly || a.top_tok == nullptr) return;
   __syncthreads();
   // merge the WAVES sorted lists: rank each of the first ktop entries of every wave
   if (lane < a.ktop) {
@@ -317,18 +329,36 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------- launchers
-static int g_waves_per_row = 4;
-void set_waves_per_row(int w) { g_waves_per_row = (w == 1 || w == 2 || w == 4 || w == 8) ? w : 4; }
+static int g_waves_per_row = 0;   // 0 = choose per launch
+void set_waves_per_row(int w) { g_waves_per_row = (w == 1 || w == 2 || w == 4 || w == 8) ? w : 0; }
 int get_waves_per_row() { return g_waves_per_row; }
+
+// One wave per row streams best when rows are long and plentiful (one threshold, one list per
+// row).  With few rows, or short ones, split a row over more waves so the chip stays full.
+static int choose_waves(int V, int blocks, int elems_per_tile) {
+  if (g_waves_per_row) return g_waves_per_row;
+  const int64_t wave_slots = 256 * 28;   // CUs x resident waves per CU at this kernel's register use
+  int w = 1;
+  while (w < 8 && (int64_t)blocks * w < wave_slots && V / (2 * w) >= 2 * elems_per_tile) w *= 2;
+  return w;
+}
+
+template <typename T, int MODE>
+static void launch_row_stats_m(const RowStatsArgs &a, int blocks, hipStream_t st) {
+  const int w = choose_waves(a.V, blocks, kWave * 4 * Elem<T>::kPerVec);
+  switch (w) {
+    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, 4, MODE>), dim3(blocks), dim3(64), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, 4, MODE>), dim3(blocks), dim3(128), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, 4, MODE>), dim3(blocks), dim3(512), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_row_stats<T, 4, 4, MODE>), dim3(blocks), dim3(256), 0, st, a); break;
+  }
+}
 
 template <typename T>
 static void launch_row_stats_t(const RowStatsArgs &a, int blocks, hipStream_t st) {
-  switch (g_waves_per_row) {
-    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, 4>), dim3(blocks), dim3(64), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, 4>), dim3(blocks), dim3(128), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, 4>), dim3(blocks), dim3(512), 0, st, a); break;
-    default: hipLaunchKernelGGL((k_row_stats<T, 4, 4>), dim3(blocks), dim3(256), 0, st, a); break;
-  }
+  if (a.top_tok == nullptr) launch_row_stats_m<T, kLseOnly>(a, blocks, st);
+  else if (a.ktop == 1) launch_row_stats_m<T, kTargetArgmax>(a, blocks, st);
+  else launch_row_stats_m<T, kDraftTopK>(a, blocks, st);
 }
 
 void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st) {

@@ -96,4 +96,4 @@ def test_validation_errors_without_gpu():
     assert _status(G.gto_ppo_surrogate_fwd, _cfg(), fd, fd, fake, fd, fake, None, fake, fd) == E["ws"]
     assert "workspace" in G.gto_strerror(E["ws"])
     assert G.gto_workspace_bytes(_cfg()) == 256
-    assert G.gto_set_waves_per_row(3) == 4 and G.gto_set_waves_per_row(2) == 2 and G.gto_set_waves_per_row(4) == 4
+    assert G.gto_set_waves_per_row(3) == 0 and G.gto_set_waves_per_row(2) == 2 and G.gto_set_waves_per_row(0) == 0

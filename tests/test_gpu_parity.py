@@ -156,7 +156,7 @@ def test_row_kernels_match_oracle(gpu_device, dtype, V, stride, waves):
         U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
         U.check_target_stats(U.to_np(ts), O.target_row_stats(Tn))
     finally:
-        G.gto_set_waves_per_row(4)
+        G.gto_set_waves_per_row(0)
 
 
 def test_rows_with_fewer_than_k_finite_logits(gpu_device):

@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--roots", type=int, default=0, help="override the number of roots (debug)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per row in the row kernels (tuning)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel (4 GiB) so that HBM counters can be scaled")
     ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -87,6 +89,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones((1 << 30,), dtype=torch.int32, device=dev)      # 4 GiB read + 4 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            G.gto_calibration_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
     G.gto_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):

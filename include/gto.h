@@ -205,6 +205,11 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur,
                           const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
                           float *grad_rows, int32_t *grad_slot, void *hip_stream);
 
+/* Measurement aid, not part of the method: copies `bytes` (a multiple of 16; both device pointers
+ * 16-byte aligned, non-overlapping) with a plain kernel.  Hardware HBM counters of the row kernels
+ * are scaled by what the same counters report for this copy of known size. */
+int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 /* Tuning knob: wavefronts that share one logits row in the row kernels (1, 2, 4 or 8; any other
  * value restores the default, a per-launch choice from V and the number of rows).  Process-wide;
  * returns the value in effect, 0 meaning the per-launch choice. */

@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     gto_version, gto_strerror, gto_workspace_bytes,
     gto_draft_row_stats, gto_target_row_stats, gto_expand_tree, gto_expand_from_stats,
     gto_select_topg, gto_tree_reward, gto_reward_from_stats, gto_group_advantage,
-    gto_ppo_surrogate_fwd, gto_ppo_surrogate_bwd, gto_set_waves_per_row,
+    gto_ppo_surrogate_fwd, gto_ppo_surrogate_bwd, gto_set_waves_per_row, gto_calibration_copy,
     gto_profile_enable, gto_profile_read,
 )

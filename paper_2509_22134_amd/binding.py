@@ -86,13 +86,14 @@ def lib():
                                         P(gto_draft_stats), VP, P(gto_ppo), VP, SZ, VP]
     L.gto_ppo_surrogate_bwd.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, P(gto_draft_stats),
                                         VP, VP, VP]
+    L.gto_calibration_copy.argtypes = [VP, VP, SZ, VP]
     L.gto_set_waves_per_row.argtypes = [C.c_int]
     L.gto_profile_enable.argtypes = [C.c_int]
     L.gto_profile_read.argtypes = [P(C.c_char_p), P(C.c_int32), P(C.c_double), C.c_int]
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
-                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read"):
+                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -269,6 +270,12 @@ def gto_ppo_surrogate_bwd(cfg, tree_cur, path_cur, fwd, draft_logits_cur, draft_
     _check(lib().gto_ppo_surrogate_bwd(C.byref(cfg), _ref(t), _ref(w), _ref(f), _dp(draft_logits_cur), _ref(ds),
                                        _dp(grad_rows), _dp(grad_slot), _stream(stream)), "gto_ppo_surrogate_bwd")
     return grad_rows, grad_slot
+
+
+def gto_calibration_copy(src, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib().gto_calibration_copy(_dp(src), _dp(dst), nbytes, _stream(stream)), "gto_calibration_copy")
+    return dst
 
 
 def gto_set_waves_per_row(waves: int) -> int:

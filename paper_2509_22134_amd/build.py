@@ -11,7 +11,7 @@ SOURCES = ["gto_api.hip", "gto_rows.hip", "gto_tree.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-ffp-contract=off", "-Wall", "-Wno-unused-command-line-argument",
+    "-ffp-contract=off", "-fno-honor-nans", "-Wall", "-Wno-unused-command-line-argument",
 ]
 
 

@@ -369,6 +369,17 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur, const
   return hip_status();
 }
 
+int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
+  if (!src || !dst) return GTO_E_NULL;
+  if (bytes == 0 || bytes % 16 != 0) return GTO_E_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return GTO_E_ALIGN;
+  {
+    ProfScope ps("calibration_copy", (hipStream_t)hip_stream);
+    gto::launch_copy16(src, dst, (int64_t)bytes, (hipStream_t)hip_stream);
+  }
+  return hip_status();
+}
+
 int gto_set_waves_per_row(int waves) {
   gto::set_waves_per_row(waves);
   return gto::get_waves_per_row();

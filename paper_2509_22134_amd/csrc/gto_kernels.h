@@ -82,6 +82,7 @@ void set_waves_per_row(int w);
 int get_waves_per_row();
 void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st);
 void launch_ppo_bwd(const PpoBwdArgs &a, int dtype, int blocks, hipStream_t st);
+void launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t st);
 void launch_expand(const ExpandArgs &a, hipStream_t st);
 void launch_select(const SelectArgs &a, hipStream_t st);
 void launch_reward(const RewardArgs &a, hipStream_t st);

@@ -328,6 +328,19 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
   if (own_tok) out[tok] = (float)((double)coef * s_part[0]);
 }
 
+// ------------------------------------------------------------------------------- calibration copy
+// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware HBM counters of the
+// row kernels are scaled by.
+__global__ __launch_bounds__(256) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t nvec) {
+  const int64_t step = (int64_t)gridDim.x * 256;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += step) dst[i] = src[i];
+}
+
+void launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t st) {
+  hipLaunchKernelGGL(k_copy16, dim3(16384), dim3(256), 0, st, static_cast<const u32x4 *>(src),
+                     static_cast<u32x4 *>(dst), bytes / 16);
+}
+
 // ------------------------------------------------------------------------------- launchers
 static int g_waves_per_row = 0;   // 0 = choose per launch
 void set_waves_per_row(int w) { g_waves_per_row = (w == 1 || w == 2 || w == 4 || w == 8) ? w : 0; }

@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--workload", default="llama31_8b")
     ap.add_argument("--roots", type=int, default=0, help="override the number of roots (debug)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per row in the row kernels (tuning)")
+    ap.add_argument("--no-prune", action="store_true",
+                    help="stream every used target row instead of only those the kept tree refers to")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel (4 GiB) so that HBM counters can be scaled")
     ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
@@ -80,7 +82,8 @@ def main():
     want = ("D_cur", "T_cur", "D_ref", "T_ref") if w.full_path else ("D_cur", "T_cur")
     tens = S.make_logits(wr, dev, want=want)        # one chunk resident; chunks reuse the buffers
     path = GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=dev,
-                   eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path)
+                   eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path,
+                   flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE)
 
     def step():
         for _ in range(n_chunks):
@@ -108,7 +111,14 @@ def main():
     trees_per_step = w.R * (2 if w.full_path else 1)
     ms_per_step = dt / args.steps * 1e3
     value = trees_per_step / (dt / args.steps)
-    fwd_bytes = S.algorithmic_bytes(w, 2 if w.full_path else 1)
+    # bytes the forward had to read: every used draft row, and the target rows actually streamed
+    row_bytes = w.V * w.elem_bytes
+    n_models = 2 if w.full_path else 1
+    if args.no_prune:
+        target_rows = n_models * R * w.rho
+    else:
+        target_rows = sum(int(path.buf[t]["tree"]["slot_need"].sum().item()) for t in path.buf)
+    fwd_bytes = n_chunks * (n_models * R * w.rho + target_rows) * row_bytes
     kernels = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in prof.items()}
     dom = "row_stats_draft"
     dom_bytes = R * w.rho * w.V * w.elem_bytes          # every used draft row once per launch
@@ -127,7 +137,9 @@ def main():
         "config": {"workload": f"{w.name}: R={w.R} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m} "
                                f"{w.dtype} logits, " + ("full path, current + reference tree per root"
                                                        if w.full_path else "reward only"),
-                   "chunks": n_chunks, "waves_per_row": args.waves or "auto"},
+                   "chunks": n_chunks, "waves_per_row": args.waves or "auto",
+                   "target_rows": "all used slots" if args.no_prune else "only slots with a kept child",
+                   "target_rows_streamed_per_chunk": target_rows, "draft_rows_per_chunk": n_models * R * w.rho},
         "logit_gb_s": fwd_bytes / (dt / args.steps) / 1e9,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -53,7 +53,12 @@ typedef enum gto_status {
 
 enum { GTO_BF16 = 0, GTO_F32 = 1 };
 enum { GTO_REWARD_LSE = 0, GTO_REWARD_MAX = 1, GTO_REWARD_MEAN = 2, GTO_REWARD_NODESUM = 3 };
-enum { GTO_FLAG_GRAD_ZERO_FILL = 1 }; /* bwd also writes zeros into rows that carry no gradient */
+enum {
+  GTO_FLAG_GRAD_ZERO_FILL = 1, /* bwd also writes zeros into rows that carry no gradient                */
+  GTO_FLAG_TARGET_PRUNE = 2    /* gto_tree_reward streams only the target rows the kept tree refers to:
+                                  slots with tree->slot_need == 0 are skipped and their entries in the
+                                  target statistics are left untouched                                 */
+};
 
 typedef struct gto_config {
   int32_t R, d, k, g, V;
@@ -105,6 +110,7 @@ typedef struct gto_tree {
   int32_t *sel_leaf;   /* 1 if no kept child                                               */
   float *sel_score;
   int32_t *n_sel;      /* [R] = min(g, C)                                                  */
+  int32_t *slot_need;  /* [R, d, k] 1 if the slot's node has a kept child (its target row is needed) */
 } gto_tree;
 
 typedef struct gto_reward {

@@ -270,7 +270,8 @@ def select_topg(pool, g: int, audit: bool = False):
     Returns dict (all [R, g], unused tail = -1 / 0): sel_cand (pool index),
     sel_tok, sel_parent (position of the parent in the kept list, -1 for depth-1
     nodes), sel_depth, sel_pslot, sel_slot, sel_leaf (1 if no kept child),
-    sel_score fp32; n_sel [R]; min_margin [R] (near-tie audit over the kept
+    sel_score fp32; n_sel [R]; slot_need [R, d, k] (1 for every slot whose node has a
+    kept child, i.e. whose target row the reward reads); min_margin [R] (near-tie audit over the kept
     order and the cut, only if audit=True; see _gap_audit).
     """
     cand_score = pool["cand_score"]
@@ -283,6 +284,8 @@ def select_topg(pool, g: int, audit: bool = False):
     sel_leaf = np.zeros((R, g), dtype=np.int32)
     sel_score = np.zeros((R, g), dtype=np.float32)
     n_sel = np.full((R,), n_keep, dtype=np.int32)
+    d_levels, k_slots = pool["slot_cand"].shape[1:]
+    slot_need = np.zeros((R, d_levels, k_slots), dtype=np.int32)
     min_margin = np.full((R,), np.inf)
     for r in range(R):
         order = _ranked(range(C), cand_score[r])
@@ -302,6 +305,8 @@ def select_topg(pool, g: int, audit: bool = False):
             sel["sel_pslot"][r, i] = pool["cand_pslot"][r, c]
             sel["sel_slot"][r, i] = pool["cand_slot"][r, c]
             sel_score[r, i] = cand_score[r, c]
+            # the target row at the parent's slot is what Eq. 4 reads for this node
+            slot_need[r, int(pool["cand_depth"][r, c]) - 1, int(pool["cand_pslot"][r, c])] = 1
         for i in range(n_keep):
             sel_leaf[r, i] = 0 if has_child[i] else 1
         if audit:
@@ -310,7 +315,7 @@ def select_topg(pool, g: int, audit: bool = False):
                        pool.get("cand_logit", [None] * R)[r], pool["cand_err"][r], margin)
             min_margin[r] = margin[0]
     out = dict(sel)
-    out.update(sel_leaf=sel_leaf, sel_score=sel_score, n_sel=n_sel, min_margin=min_margin)
+    out.update(sel_leaf=sel_leaf, sel_score=sel_score, n_sel=n_sel, slot_need=slot_need, min_margin=min_margin)
     return out
 
 

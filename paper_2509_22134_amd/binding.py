@@ -10,9 +10,10 @@ import torch
 GTO_BF16, GTO_F32 = 0, 1
 GTO_REWARD_LSE, GTO_REWARD_MAX, GTO_REWARD_MEAN, GTO_REWARD_NODESUM = 0, 1, 2, 3
 GTO_FLAG_GRAD_ZERO_FILL = 1
+GTO_FLAG_TARGET_PRUNE = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libgto.so")
+_LIB_PATH = os.environ.get("GTO_LIB_PATH") or os.path.join(_HERE, "libgto.so")   # override: tuning builds
 _lib = None
 
 
@@ -44,7 +45,8 @@ def _ptr_struct(name, fields):
 _DRAFT = ("row_max", "row_lse", "top_tok", "top_logp")
 _TARGET = ("t_max", "t_lse", "t_argmax")
 _POOL = ("cand_tok", "cand_parent", "cand_depth", "cand_pslot", "cand_slot", "cand_score", "slot_cand")
-_TREE = ("sel_cand", "sel_tok", "sel_parent", "sel_depth", "sel_pslot", "sel_slot", "sel_leaf", "sel_score", "n_sel")
+_TREE = ("sel_cand", "sel_tok", "sel_parent", "sel_depth", "sel_pslot", "sel_slot", "sel_leaf", "sel_score", "n_sel",
+         "slot_need")
 _REWARD = ("node_q", "node_cum", "reward", "reward_aux", "n_leaves", "path_len", "path_node", "path_slot")
 _PPO = ("logM", "logM0", "ratio", "term", "active", "coef", "loss_group", "loss")
 gto_draft_stats = _ptr_struct("gto_draft_stats", _DRAFT)
@@ -137,6 +139,7 @@ def alloc_tree(cfg, device):
     spec = {n: (s, torch.int32) for n in _TREE[:7]}
     spec["sel_score"] = (s, torch.float32)
     spec["n_sel"] = ((cfg.R,), torch.int32)
+    spec["slot_need"] = ((cfg.R, cfg.d, cfg.k), torch.int32)
     return _alloc(spec, device)
 
 

@@ -15,13 +15,20 @@ FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False, extra=()) -> str:
+def build_lib(verbose: bool = False, extra=(), out: str = LIB) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    cmd = [hipcc, *FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return LIB
+    # hipcc's host pass prints one line per file about the device-only target feature: harmless
+    res = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    noise = "'-packed-fp32-ops' is not a recognized feature"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if err.strip():
+        print(err, flush=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed with status {res.returncode}")
+    return out
 
 
 if __name__ == "__main__":

@@ -106,7 +106,7 @@ int check_pool(const gto_pool *p) {
 }
 int check_tree(const gto_tree *t) {
   if (!t || any_null({t->sel_cand, t->sel_tok, t->sel_parent, t->sel_depth, t->sel_pslot, t->sel_slot,
-                      t->sel_leaf, t->sel_score, t->n_sel}))
+                      t->sel_leaf, t->sel_score, t->n_sel, t->slot_need}))
     return GTO_E_NULL;
   return GTO_OK;
 }
@@ -134,12 +134,14 @@ void run_draft_rows(const gto_config *c, const void *logits, const gto_draft_sta
   gto::launch_row_stats(a, c->dtype, c->R * a.rho, st);
 }
 
-void run_target_rows(const gto_config *c, const void *logits, const gto_target_stats *s, hipStream_t st) {
+void run_target_rows(const gto_config *c, const void *logits, const gto_target_stats *s,
+                     const int32_t *row_need, hipStream_t st) {
   gto::RowStatsArgs a{};
   a.logits = logits;
   a.row_stride = c->row_stride;
   a.V = c->V; a.d = c->d; a.kslots = c->k; a.ktop = 1; a.rho = rows_per_root(c);
   a.path_slot = nullptr;
+  a.row_need = row_need;
   a.row_max = s->t_max; a.row_lse = s->t_lse; a.top_tok = s->t_argmax; a.top_logp = nullptr;
   ProfScope ps("row_stats_target", st);
   gto::launch_row_stats(a, c->dtype, c->R * a.rho, st);
@@ -212,7 +214,7 @@ int gto_target_row_stats(const gto_config *cfg, const void *target_logits, const
   GTO_TRY(check_cfg(cfg, false));
   GTO_TRY(check_logits(target_logits));
   GTO_TRY(check_target_stats(stats_out));
-  run_target_rows(cfg, target_logits, stats_out, (hipStream_t)hip_stream);
+  run_target_rows(cfg, target_logits, stats_out, nullptr, (hipStream_t)hip_stream);
   return hip_status();
 }
 
@@ -243,12 +245,13 @@ int gto_select_topg(const gto_config *cfg, const gto_pool *pool, const gto_tree 
   GTO_TRY(check_pool(pool));
   GTO_TRY(check_tree(tree_out));
   gto::SelectArgs a{};
-  a.R = cfg->R; a.C = pool_size(cfg); a.g = cfg->g;
+  a.R = cfg->R; a.C = pool_size(cfg); a.g = cfg->g; a.d = cfg->d; a.k = cfg->k;
   a.cand_tok = pool->cand_tok; a.cand_parent = pool->cand_parent; a.cand_depth = pool->cand_depth;
   a.cand_pslot = pool->cand_pslot; a.cand_slot = pool->cand_slot; a.cand_score = pool->cand_score;
   a.sel_cand = tree_out->sel_cand; a.sel_tok = tree_out->sel_tok; a.sel_parent = tree_out->sel_parent;
   a.sel_depth = tree_out->sel_depth; a.sel_pslot = tree_out->sel_pslot; a.sel_slot = tree_out->sel_slot;
   a.sel_leaf = tree_out->sel_leaf; a.sel_score = tree_out->sel_score; a.n_sel = tree_out->n_sel;
+  a.slot_need = tree_out->slot_need;
   {
     ProfScope ps("select_topg", (hipStream_t)hip_stream);
     gto::launch_select(a, (hipStream_t)hip_stream);
@@ -277,7 +280,8 @@ int gto_tree_reward(const gto_config *cfg, const gto_tree *tree, const void *tar
   GTO_TRY(check_tree(tree));
   GTO_TRY(check_target_stats(stats_out));
   GTO_TRY(check_reward(reward_out));
-  run_target_rows(cfg, target_logits, stats_out, (hipStream_t)hip_stream);
+  run_target_rows(cfg, target_logits, stats_out,
+                  (cfg->flags & GTO_FLAG_TARGET_PRUNE) ? tree->slot_need : nullptr, (hipStream_t)hip_stream);
   run_reward(cfg, tree, target_logits, stats_out, reward_out, (hipStream_t)hip_stream);
   return hip_status();
 }

@@ -10,6 +10,7 @@ struct RowStatsArgs {
   int64_t row_stride;
   int V, d, kslots, ktop, rho;
   const int32_t *path_slot;  // null: all used slots; else rows (root, step) on an accepted path
+  const int32_t *row_need;   // optional [R, d, kslots]: rows whose flag is 0 are skipped
   float *row_max;            // may be null
   float *row_lse;
   int32_t *top_tok;          // may be null (then no top-k output)
@@ -37,12 +38,12 @@ struct ExpandArgs {
 };
 
 struct SelectArgs {
-  int R, C, g;
+  int R, C, g, d, k;
   const int32_t *cand_tok, *cand_parent, *cand_depth, *cand_pslot, *cand_slot;
   const float *cand_score;
   int32_t *sel_cand, *sel_tok, *sel_parent, *sel_depth, *sel_pslot, *sel_slot, *sel_leaf;
   float *sel_score;
-  int32_t *n_sel;
+  int32_t *n_sel, *slot_need;
 };
 
 struct RewardArgs {

@@ -13,6 +13,13 @@
 #include "gto_device.h"
 #include "gto_kernels.h"
 
+#ifndef GTO_ROW_LOADS
+#define GTO_ROW_LOADS 4
+#endif
+#ifndef GTO_ROW_PREFETCH
+#define GTO_ROW_PREFETCH 0
+#endif
+
 namespace gto {
 
 // ----------------------------------------------------------------------------- top-k list
@@ -55,14 +62,10 @@ struct LaneAcc {
 
 enum RowMode { kDraftTopK = 0, kTargetArgmax = 1, kLseOnly = 2 };
 
-template <typename T, int LOADS, bool GUARD, int MODE>
-__device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_base, int V, int lane,
-                                          int ktop_rt, bool &first, LaneAcc &acc, TopList &top,
-                                          float &thr_v, int &thr_i) {
-  const int ktop = (MODE == kTargetArgmax) ? 1 : ktop_rt;
+// Issues the LOADS 16-byte loads of one tile (lane l, load u: elements (u*64 + l)*EPV ...).
+template <typename T, int LOADS, bool GUARD>
+__device__ __forceinline__ void load_tile(const T *__restrict__ row, int tile_base, int V, int lane, u32x4 *q) {
   constexpr int EPV = Elem<T>::kPerVec;
-  float x[LOADS][EPV];
-  u32x4 q[LOADS];
 #pragma unroll
   for (int u = 0; u < LOADS; ++u) {
     const int e0 = tile_base + (u * kWave + lane) * EPV;
@@ -72,6 +75,15 @@ __device__ __forceinline__ void scan_tile(const T *__restrict__ row, int tile_ba
       q[u] = u32x4{0u, 0u, 0u, 0u};
     }
   }
+}
+
+template <typename T, int LOADS, bool GUARD, int MODE>
+__device__ __forceinline__ void scan_tile(const u32x4 *q, int tile_base, int V, int lane,
+                                          int ktop_rt, bool &first, LaneAcc &acc, TopList &top,
+                                          float &thr_v, int &thr_i) {
+  const int ktop = (MODE == kTargetArgmax) ? 1 : ktop_rt;
+  constexpr int EPV = Elem<T>::kPerVec;
+  float x[LOADS][EPV];
 #pragma unroll
   for (int u = 0; u < LOADS; ++u) {
     Elem<T>::unpack(q[u], x[u]);
@@ -167,6 +179,7 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
     l = (qq == 0) ? 0 : 1 + (qq - 1) / a.kslots;
     j = (qq == 0) ? 0 : (qq - 1) % a.kslots;
     oi = stat_index(r, l, j, a.d, a.kslots);
+    if (a.row_need != nullptr && a.row_need[oi] == 0) return;
   } else {  // rows on an accepted path: block = (root, step)
     r = blockIdx.x / a.d;
     l = blockIdx.x - r * a.d;
@@ -186,10 +199,33 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
   bool first = true;
 
   const int n_full = V / TILE;
-  for (int t = wave; t < n_full; t += WAVES)
-    scan_tile<T, LOADS, false, MODE>(row, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
-  if (n_full * TILE < V && (n_full % WAVES) == wave)
-    scan_tile<T, LOADS, true, MODE>(row, n_full * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+#if GTO_ROW_PREFETCH
+  // software pipeline: the loads of the next tile are in flight while this one is processed
+  if (wave < n_full) {
+    u32x4 qa[LOADS], qb[LOADS];
+    load_tile<T, LOADS, false>(row, wave * TILE, V, lane, qa);
+    for (int t = wave; t < n_full; t += WAVES) {
+      const bool more = (t + WAVES < n_full);
+      if (more) load_tile<T, LOADS, false>(row, (t + WAVES) * TILE, V, lane, qb);
+      scan_tile<T, LOADS, false, MODE>(qa, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+      if (more) {
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) qa[u] = qb[u];
+      }
+    }
+  }
+#else
+  for (int t = wave; t < n_full; t += WAVES) {
+    u32x4 q[LOADS];
+    load_tile<T, LOADS, false>(row, t * TILE, V, lane, q);
+    scan_tile<T, LOADS, false, MODE>(q, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+  }
+#endif
+  if (n_full * TILE < V && (n_full % WAVES) == wave) {
+    u32x4 q[LOADS];
+    load_tile<T, LOADS, true>(row, n_full * TILE, V, lane, q);
+    scan_tile<T, LOADS, true, MODE>(q, n_full * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
+  }
 
   // wave-level reduction of (max, offset, sum)
   const float Mw = wave_max(acc.m);
@@ -356,14 +392,15 @@ static int choose_waves(int V, int blocks, int elems_per_tile) {
   return w;
 }
 
+
 template <typename T, int MODE>
 static void launch_row_stats_m(const RowStatsArgs &a, int blocks, hipStream_t st) {
-  const int w = choose_waves(a.V, blocks, kWave * 4 * Elem<T>::kPerVec);
+  const int w = choose_waves(a.V, blocks, kWave * GTO_ROW_LOADS * Elem<T>::kPerVec);
   switch (w) {
-    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, 4, MODE>), dim3(blocks), dim3(64), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, 4, MODE>), dim3(blocks), dim3(128), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, 4, MODE>), dim3(blocks), dim3(512), 0, st, a); break;
-    default: hipLaunchKernelGGL((k_row_stats<T, 4, 4, MODE>), dim3(blocks), dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(64), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(128), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(512), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_row_stats<T, 4, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(256), 0, st, a); break;
   }
 }
 

@@ -93,10 +93,12 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
   __shared__ uint64_t s_key[kMaxPool];
   __shared__ int s_rank[kMaxPool];
   __shared__ unsigned char s_leaf[kMaxPool];
+  __shared__ unsigned char s_need[32 * 64];   // d * k flags
   const int64_t pool0 = (int64_t)r * C;
   const int64_t sel0 = (int64_t)r * g;
   for (int c = tid; c < C; c += kTreeThreads) s_key[c] = rank_key(a.cand_score[pool0 + c], c);
   for (int i = tid; i < n_keep; i += kTreeThreads) s_leaf[i] = 1;
+  for (int i = tid; i < a.d * a.k; i += kTreeThreads) s_need[i] = 0;
   __syncthreads();
   for (int c = tid; c < C; c += kTreeThreads) {
     const uint64_t mine = s_key[c];
@@ -111,6 +113,8 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
       const int pr = s_rank[p];
       if (pr < n_keep) s_leaf[pr] = 0;  // a kept child: the parent is not a leaf
     }
+    // the row that produced a kept node is needed by the reward
+    if (s_rank[c] < n_keep) s_need[(a.cand_depth[pool0 + c] - 1) * a.k + a.cand_pslot[pool0 + c]] = 1;
   }
   __syncthreads();
   for (int c = tid; c < C; c += kTreeThreads) {
@@ -137,6 +141,7 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
     a.sel_score[sel0 + i] = 0.f;
     a.sel_leaf[sel0 + i] = 0;
   }
+  for (int i = tid; i < a.d * a.k; i += kTreeThreads) a.slot_need[(int64_t)r * a.d * a.k + i] = s_need[i];
   if (tid == 0) a.n_sel[r] = n_keep;
 }
 

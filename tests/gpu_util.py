@@ -47,7 +47,7 @@ def check_target_stats(gt, ot, lse_rtol=1e-6):
 
 
 INT_POOL = ("cand_tok", "cand_parent", "cand_depth", "cand_pslot", "cand_slot", "slot_cand")
-INT_TREE = ("sel_cand", "sel_tok", "sel_parent", "sel_depth", "sel_pslot", "sel_slot", "sel_leaf", "n_sel")
+INT_TREE = ("sel_cand", "sel_tok", "sel_parent", "sel_depth", "sel_pslot", "sel_slot", "sel_leaf", "n_sel", "slot_need")
 INT_PATH = ("path_len", "path_node", "path_slot")
 
 

@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     assert C.sizeof(B.gto_config) == 64
     assert B.gto_config.row_stride.offset == 24
-    assert C.sizeof(B.gto_tree) == 9 * 8 and C.sizeof(B.gto_reward) == 8 * 8
+    assert C.sizeof(B.gto_tree) == 10 * 8 and C.sizeof(B.gto_reward) == 8 * 8
 
 
 def _cfg(**kw):

@@ -242,6 +242,33 @@ def test_reward_modes_and_no_debias(gpu_device, mode, key):
                                rtol=2e-6, atol=1e-6)
 
 
+def test_target_row_pruning_changes_nothing_but_the_rows_read(gpu_device):
+    _say("target-row pruning")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=16000)
+    tens = S.make_logits(w, gpu_device)
+    a = _run_full(w, tens, gpu_device)
+    b = _run_full(w, tens, gpu_device, flags=G.GTO_FLAG_TARGET_PRUNE)
+    b.grad_rows.copy_(a.grad_rows)                      # (rows without gradient are untouched in both)
+    b.step(tens["D_cur"], tens["T_cur"], tens["D_ref"], tens["T_ref"])
+    torch.cuda.synchronize()
+    for tag in ("cur", "ref"):
+        need = a.buf[tag]["tree"]["slot_need"].bool()
+        assert torch.equal(need, b.buf[tag]["tree"]["slot_need"].bool())
+        frac = need.float().sum().item() / (16 * w.rho)
+        _say(f"  {tag}: {frac:.2f} of the target rows are needed")
+        assert 0.05 < frac < 0.95 and bool(need[:, 0, 0].all()) and not bool(need[:, 0, 1:].any())
+        for n, t in a.buf[tag]["tstats"].items():
+            assert torch.equal(t[need], b.buf[tag]["tstats"][n][need]), n
+            assert not b.buf[tag]["tstats"][n][~need].any(), n      # skipped rows were never written
+        for grp in ("tree", "reward"):
+            for n, t in a.buf[tag][grp].items():
+                assert torch.equal(t, b.buf[tag][grp][n]), (tag, grp, n)
+    for n, t in a.ppo.items():
+        assert torch.equal(t, b.ppo[n]), n
+    assert torch.equal(a.grad_slot, b.grad_slot) and torch.equal(a.grad_rows, b.grad_rows)
+    _compare_all(w, tens, a)                              # slot_need itself is checked against the oracle here
+
+
 def test_bitwise_deterministic(gpu_device):
     _say("determinism")
     w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=16000)

@@ -209,6 +209,78 @@ def make_logits(w: Workload, device, want=("D_cur", "T_cur", "D_ref", "T_ref"),
     return out
 
 
+# ----------------------------------------------------------------------------- fused LM-head workload
+@dataclasses.dataclass(frozen=True)
+class FusedWorkload:
+    """Hidden states and LM heads instead of logits: D = H . W_draft^T, T = H . W_target^T.
+    H_cur ~ N(0, h_scale^2) (seed); H_ref = H_cur + N(0, ref_sigma^2) from the second seed (None: an
+    independent draw); W_draft ~ N(0, w_sigma^2) (seed), W_target = corr * W_draft + sqrt(1 - corr^2) *
+    N(0, w_sigma^2) (seed + 1); corr = 0 is the independent second head of the fifth configuration.
+    Weights are stored vocabulary-major, [V, hidden]."""
+    name: str
+    R: int
+    V: int
+    k: int
+    d: int
+    g: int
+    m: int
+    hidden: int
+    h_scale: float = 1.0
+    w_sigma: float = 0.02
+    w_corr: float = 0.0
+    ref_sigma: Optional[float] = 0.07
+    seed: int = BASE_SEED + 5
+    eta: float = 1.0
+    eps: float = 0.2
+    delta: float = 1e-6
+    dtype: str = "bf16"
+    full_path: bool = True
+
+    @property
+    def rho(self) -> int:
+        return 1 + (self.d - 1) * self.k
+
+    @property
+    def C(self) -> int:
+        return self.k + (self.d - 1) * self.k * self.k
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16
+
+
+FUSED_CONFIGS: Dict[str, FusedWorkload] = {
+    "llama33_70b_fused": FusedWorkload("llama33_70b_fused", R=1024, V=128256, k=8, d=8, g=80, m=8, hidden=8192),
+}
+
+
+def make_fused(w: FusedWorkload, device) -> Dict[str, torch.Tensor]:
+    device = torch.device(device)
+    s0 = w.seed * 1000003
+    s1 = (w.seed + 1) * 1000003
+    shape = (w.R, w.d, w.k, w.hidden)
+    H_cur = _noise(shape, w.h_scale, device, s0 + 1)
+    if w.ref_sigma is None:
+        H_ref = _noise(shape, w.h_scale, device, s1 + 1)
+    else:
+        H_ref = H_cur + _noise(shape, w.ref_sigma, device, s1 + 1)
+    out = {"H_cur": H_cur.to(torch.bfloat16), "H_ref": H_ref.to(torch.bfloat16)}
+    del H_cur, H_ref
+    rows = max(1, (1 << 28) // w.hidden)                      # generate the heads in ~1 GiB fp32 blocks
+    W_d = torch.empty((w.V, w.hidden), dtype=torch.bfloat16, device=device)
+    W_t = torch.empty((w.V, w.hidden), dtype=torch.bfloat16, device=device)
+    c = float(w.w_corr)
+    for v0 in range(0, w.V, rows):
+        v1 = min(v0 + rows, w.V)
+        wd = _noise((v1 - v0, w.hidden), w.w_sigma, device, s0 + 11 + v0)
+        wt = _noise((v1 - v0, w.hidden), w.w_sigma, device, s1 + 11 + v0)
+        W_d[v0:v1] = wd.to(torch.bfloat16)
+        W_t[v0:v1] = (c * wd + math.sqrt(max(0.0, 1.0 - c * c)) * wt).to(torch.bfloat16)
+    out["W_draft"] = W_d
+    out["W_target"] = W_t
+    return out
+
+
 def algorithmic_bytes(w: Workload, n_models: int = 2) -> int:
     """Bytes the forward path must read: every used draft row and every used
     target row once, for `n_models` trees per root."""

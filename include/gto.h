@@ -211,6 +211,54 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur,
                           const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
                           float *grad_rows, int32_t *grad_slot, void *hip_stream);
 
+/* ---- Fused LM-head variant (the fifth workload: logits never reach HBM) -------------------------
+ * The logits of slot (l, j) of root r are hidden[r, l, j, :] . w_vh[v, :] for v < V, accumulated in
+ * fp32 on the matrix cores and consumed as fp32 (never rounded to bf16).  `hidden` is bf16
+ * [R, d, k, hidden_dim]; `w_vh` is the LM-head weight bf16 [V, hidden_dim] (vocabulary-major, the
+ * layout a linear layer stores).  Requirements: cfg->dtype == GTO_BF16, k <= 16, hidden_dim a
+ * multiple of 64, both pointers 16-byte aligned.  `workspace` (device, 256-byte aligned) must hold
+ * gto_fused_workspace_bytes(cfg, hidden_dim) bytes. */
+int gto_fused_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out);
+
+/* Same outputs as gto_draft_row_stats / gto_target_row_stats, from hidden states and the LM head.
+ * `top_logit_or_null` [R, d, k, k] optionally receives the fp32 logits of the top-k tokens. */
+int gto_fused_draft_row_stats(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_vh,
+                              const gto_draft_stats *stats_out, float *top_logit_or_null, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
+int gto_fused_target_row_stats(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_vh,
+                               const gto_target_stats *stats_out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/* gto_expand_tree / gto_tree_reward / gto_ppo_surrogate_fwd with the logits produced on the fly.
+ * Single logits that the reward (kept tokens under the target) and the surrogate (path tokens under
+ * the current and the reference draft) need are recomputed as fp32 dot products.  In the surrogate,
+ * `hidden_ref_on_cur` holds the reference model's hidden states at the current tree's slot
+ * coordinates and `ref_stats` (required) its row statistics under the same draft head. */
+int gto_expand_tree_fused(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_draft_vh,
+                          const gto_draft_stats *stats_out, const gto_pool *pool_out, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const void *hidden, int32_t hidden_dim,
+                          const void *w_target_vh, const gto_target_stats *stats_out,
+                          const gto_reward *reward_out, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+int gto_ppo_surrogate_fwd_fused(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                const void *hidden_cur, const void *hidden_ref_on_cur, int32_t hidden_dim,
+                                const void *w_draft_vh, const gto_draft_stats *draft_stats_cur,
+                                const gto_draft_stats *ref_stats, const float *adv, const gto_ppo *out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* gto_ppo_surrogate_bwd with the logits of the path rows recomputed on the matrix cores: same
+ * grad_rows [R, d, V] / grad_slot [R, d] outputs and flag semantics.  Only the (root, step) pairs
+ * that carry a gradient are multiplied. */
+int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                const gto_ppo *fwd, const void *hidden_cur, int32_t hidden_dim,
+                                const void *w_draft_vh, const gto_draft_stats *draft_stats_cur, float *grad_rows,
+                                int32_t *grad_slot, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Tuning knob of the fused kernels: vocabulary chunks per row block (0 = per-launch choice) and
+ * whether workgroups are laid out in per-XCD patches (default 1).  Process-wide. */
+int gto_set_fused_tuning(int n_chunks, int xcd_patches);
+
 /* Measurement aid, not part of the method: copies `bytes` (a multiple of 16; both device pointers
  * 16-byte aligned, non-overlapping) with a plain kernel.  Hardware HBM counters of the row kernels
  * are scaled by what the same counters report for this copy of known size. */

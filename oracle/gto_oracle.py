@@ -67,6 +67,36 @@ def pool_size(d: int, k: int) -> int:
 
 
 # --------------------------------------------------------------------------- rows
+def fused_logits(H: np.ndarray, W_vh: np.ndarray) -> np.ndarray:
+    """Logits of the fused LM-head workload: logits[r, l, j, v] = sum_h H[r, l, j, h] * W_vh[v, h], in
+    fp64 (inputs are bf16 values, so every product is exact and only the fp64 sum rounds).  Rows of
+    padding slots are left at zero; they are never read."""
+    R, d, k, Hd = H.shape
+    V = W_vh.shape[0]
+    Wt = np.ascontiguousarray(W_vh.astype(np.float64).T)
+    out = np.zeros((R, d, k, V))
+    for r in range(R):
+        for (l, j) in used_slots(d, k):
+            out[r, l, j] = H[r, l, j].astype(np.float64) @ Wt
+    return out
+
+
+def row_margins(logits: np.ndarray, k: int, logit_err: float) -> np.ndarray:
+    """Near-tie audit of the per-row top-k when the logits themselves carry an error of up to
+    `logit_err` (fp32 accumulation on the other side): per root, the smallest gap between
+    neighbours among the k+1 largest logits of any used row, divided by 2 * logit_err.  Below 1
+    the order of that row's top-k (or its cut) may legitimately differ."""
+    R, d, kk, V = logits.shape
+    out = np.full((R,), np.inf)
+    for r in range(R):
+        for (l, j) in used_slots(d, kk):
+            top = np.sort(logits[r, l, j])[::-1][: k + 1]
+            gaps = top[:-1] - top[1:]
+            if len(gaps):
+                out[r] = min(out[r], float(gaps.min()) / (2.0 * logit_err))
+    return out
+
+
 def _row_lse(x64: np.ndarray):
     m = float(np.max(x64))
     s = float(np.sum(np.exp(x64 - m)))
@@ -168,7 +198,7 @@ def _gap_audit(order, upto, score64, parent, logit, err, margin):
     return margin
 
 
-def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=None):
+def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=None, logit_err: float = 0.0):
     """Stage (i) of the decoding policy G: layer-wise expansion.
 
     Level 0: the root (path confidence 1.0, i.e. score 0) proposes k children,
@@ -186,7 +216,9 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
     its sum of exponentials is only accurate to fp32 relative precision, and each
     fp32 add rounds by half an ulp); `min_margin[r]` is then the smallest
     gap-to-budget ratio (see _gap_audit) over the ranking decisions of root r:
-    >= 1 means every decision of that root is clear of fp32 rounding.
+    >= 1 means every decision of that root is clear of fp32 rounding.  `logit_err` adds, per
+    level, twice an absolute error of the logits themselves (fused LM-head workload, where the
+    other side accumulates the logits in fp32): once for the logit, once for the row's lse.
 
     Returns dict: cand_tok, cand_parent (pool index or -1), cand_depth (1..d),
     cand_pslot (slot j of the parent within its level), cand_slot (slot the node
@@ -220,7 +252,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
             cand_pslot[r, c] = 0
             cand_score[r, c] = np.float32(0.0) + np.float32(top_logp32[r, 0, 0, rank])
             cand_score64[r, c] = lp64[r, 0, 0, rank]
-            cand_err[r, c] = _ulp32(top_logp32[r, 0, 0, rank]) + SUM_REL_ERR
+            cand_err[r, c] = _ulp32(top_logp32[r, 0, 0, rank]) + SUM_REL_ERR + 2.0 * logit_err
             if top_logit is not None:
                 cand_logit[r, c] = top_logit[r, 0, 0, rank]
         if d > 1:
@@ -239,7 +271,7 @@ def expand_tree(top_tok, top_logp32, d: int, k: int, top_logp64=None, top_logit=
                     cand_pslot[r, c] = j
                     cand_score[r, c] = np.float32(cand_score[r, p]) + np.float32(top_logp32[r, l, j, rank])
                     cand_score64[r, c] = cand_score64[r, p] + lp64[r, l, j, rank]
-                    cand_err[r, c] = cand_err[r, p] + _ulp32(top_logp32[r, l, j, rank]) + SUM_REL_ERR \
+                    cand_err[r, c] = cand_err[r, p] + _ulp32(top_logp32[r, l, j, rank]) + SUM_REL_ERR + 2.0 * logit_err \
                         + 0.5 * _ulp32(cand_score[r, c])
                     if top_logit is not None:
                         cand_logit[r, c] = top_logit[r, l, j, rank]
@@ -507,14 +539,14 @@ def ppo_surrogate_bwd(path, tree, fwd, D_cur, d_lse, adv, m: int, grad_scale: fl
 
 # ------------------------------------------------------------------------ whole path
 def full_path(D_cur, T_cur, D_ref, T_ref, *, k, d, g, m, eta=1.0, eps=0.2, delta=1e-6,
-              grad_scale=1.0, reward_mode="lse", want_grad=True):
+              grad_scale=1.0, reward_mode="lse", want_grad=True, logit_err=0.0):
     """Algorithm 1, lines for one minibatch of R roots, composed from the steps
     above.  D_ref doubles as the reference model's logits at the current tree's
     slot coordinates (Eq. 11 denominator)."""
     out = {}
     for tag, D, T in (("cur", D_cur, T_cur), ("ref", D_ref, T_ref)):
         ds = draft_row_stats(D, k)
-        pool = expand_tree(ds["top_tok"], ds["top_logp32"], d, k, ds["top_logp64"], ds["top_logit"])
+        pool = expand_tree(ds["top_tok"], ds["top_logp32"], d, k, ds["top_logp64"], ds["top_logit"], logit_err)
         tree = select_topg(pool, g, audit=True)
         ts = target_row_stats(T)
         rew = tree_reward(tree, T, ts["t_lse"], eta)

@@ -89,13 +89,27 @@ def lib():
     L.gto_ppo_surrogate_bwd.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, P(gto_draft_stats),
                                         VP, VP, VP]
     L.gto_calibration_copy.argtypes = [VP, VP, SZ, VP]
+    L.gto_fused_workspace_bytes.argtypes = [cfgp, C.c_int32, P(SZ)]
+    L.gto_fused_draft_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), VP, VP, SZ, VP]
+    L.gto_fused_target_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_target_stats), VP, SZ, VP]
+    L.gto_set_fused_tuning.argtypes = [C.c_int, C.c_int]
+    L.gto_expand_tree_fused.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), P(gto_pool), VP, SZ, VP]
+    L.gto_tree_reward_fused.argtypes = [cfgp, P(gto_tree), VP, C.c_int32, VP, P(gto_target_stats), P(gto_reward),
+                                        VP, SZ, VP]
+    L.gto_ppo_surrogate_bwd_fused.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, C.c_int32, VP,
+                                              P(gto_draft_stats), VP, VP, VP, SZ, VP]
+    L.gto_ppo_surrogate_fwd_fused.argtypes = [cfgp, P(gto_tree), P(gto_reward), VP, VP, C.c_int32, VP,
+                                              P(gto_draft_stats), P(gto_draft_stats), VP, P(gto_ppo), VP, SZ, VP]
     L.gto_set_waves_per_row.argtypes = [C.c_int]
     L.gto_profile_enable.argtypes = [C.c_int]
     L.gto_profile_read.argtypes = [P(C.c_char_p), P(C.c_int32), P(C.c_double), C.c_int]
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
-                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy"):
+                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy",
+                 "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
+                 "gto_set_fused_tuning", "gto_expand_tree_fused", "gto_tree_reward_fused",
+                 "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -273,6 +287,77 @@ def gto_ppo_surrogate_bwd(cfg, tree_cur, path_cur, fwd, draft_logits_cur, draft_
     _check(lib().gto_ppo_surrogate_bwd(C.byref(cfg), _ref(t), _ref(w), _ref(f), _dp(draft_logits_cur), _ref(ds),
                                        _dp(grad_rows), _dp(grad_slot), _stream(stream)), "gto_ppo_surrogate_bwd")
     return grad_rows, grad_slot
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _dp(workspace), workspace.numel() * workspace.element_size()
+
+
+def gto_fused_workspace_bytes(cfg, hidden_dim: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().gto_fused_workspace_bytes(C.byref(cfg), hidden_dim, C.byref(out)), "gto_fused_workspace_bytes")
+    return out.value
+
+
+def gto_fused_draft_row_stats(cfg, hidden, w_vh, stats, workspace, top_logit=None, stream=None):
+    s = _pack(gto_draft_stats, _DRAFT, stats)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_fused_draft_row_stats(C.byref(cfg), _dp(hidden), hidden.shape[-1], _dp(w_vh), _ref(s),
+                                           _dp(top_logit), ws, wb, _stream(stream)), "gto_fused_draft_row_stats")
+    return stats
+
+
+def gto_fused_target_row_stats(cfg, hidden, w_vh, stats, workspace, stream=None):
+    s = _pack(gto_target_stats, _TARGET, stats)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_fused_target_row_stats(C.byref(cfg), _dp(hidden), hidden.shape[-1], _dp(w_vh), _ref(s),
+                                            ws, wb, _stream(stream)), "gto_fused_target_row_stats")
+    return stats
+
+
+def gto_expand_tree_fused(cfg, hidden, w_draft_vh, stats, pool, workspace, stream=None):
+    s, p = _pack(gto_draft_stats, _DRAFT, stats), _pack(gto_pool, _POOL, pool)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_expand_tree_fused(C.byref(cfg), _dp(hidden), hidden.shape[-1], _dp(w_draft_vh), _ref(s), _ref(p),
+                                       ws, wb, _stream(stream)), "gto_expand_tree_fused")
+    return stats, pool
+
+
+def gto_tree_reward_fused(cfg, tree, hidden, w_target_vh, stats, reward, workspace, stream=None):
+    t, s, w = _pack(gto_tree, _TREE, tree), _pack(gto_target_stats, _TARGET, stats), _pack(gto_reward, _REWARD, reward)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_tree_reward_fused(C.byref(cfg), _ref(t), _dp(hidden), hidden.shape[-1], _dp(w_target_vh), _ref(s),
+                                       _ref(w), ws, wb, _stream(stream)), "gto_tree_reward_fused")
+    return stats, reward
+
+
+def gto_ppo_surrogate_fwd_fused(cfg, tree_cur, path_cur, hidden_cur, hidden_ref_on_cur, w_draft_vh, draft_stats_cur,
+                                ref_stats, adv, out, workspace, stream=None):
+    t, w = _pack(gto_tree, _TREE, tree_cur), _pack(gto_reward, _REWARD, path_cur)
+    ds, rs = _pack(gto_draft_stats, _DRAFT, draft_stats_cur), _pack(gto_draft_stats, _DRAFT, ref_stats)
+    o = _pack(gto_ppo, _PPO, out)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_ppo_surrogate_fwd_fused(C.byref(cfg), _ref(t), _ref(w), _dp(hidden_cur), _dp(hidden_ref_on_cur),
+                                             hidden_cur.shape[-1], _dp(w_draft_vh), _ref(ds), _ref(rs), _dp(adv),
+                                             _ref(o), ws, wb, _stream(stream)), "gto_ppo_surrogate_fwd_fused")
+    return out
+
+
+def gto_ppo_surrogate_bwd_fused(cfg, tree_cur, path_cur, fwd, hidden_cur, w_draft_vh, draft_stats_cur, grad_rows,
+                                grad_slot, workspace, stream=None):
+    t, w = _pack(gto_tree, _TREE, tree_cur), _pack(gto_reward, _REWARD, path_cur)
+    f, ds = _pack(gto_ppo, _PPO, fwd), _pack(gto_draft_stats, _DRAFT, draft_stats_cur)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_ppo_surrogate_bwd_fused(C.byref(cfg), _ref(t), _ref(w), _ref(f), _dp(hidden_cur),
+                                             hidden_cur.shape[-1], _dp(w_draft_vh), _ref(ds), _dp(grad_rows),
+                                             _dp(grad_slot), ws, wb, _stream(stream)), "gto_ppo_surrogate_bwd_fused")
+    return grad_rows, grad_slot
+
+
+def gto_set_fused_tuning(n_chunks: int = 0, xcd_patches: bool = True) -> None:
+    _check(lib().gto_set_fused_tuning(int(n_chunks), 1 if xcd_patches else 0), "gto_set_fused_tuning")
 
 
 def gto_calibration_copy(src, dst, stream=None):

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgto.so")
-SOURCES = ["gto_api.hip", "gto_rows.hip", "gto_tree.hip"]
+SOURCES = ["gto_api.hip", "gto_rows.hip", "gto_tree.hip", "gto_fused.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -172,6 +172,128 @@ void run_reward(const gto_config *c, const gto_tree *t, const void *logits, cons
   gto::launch_reward(a, st);
 }
 
+// ------------------------------------------------------------------------- fused LM-head variant
+constexpr int kFusedMaxK = 16;
+int g_fused_chunks = 0;        // 0 = choose per launch
+int g_fused_patches = 1;
+
+struct FusedPlan {
+  int64_t M;
+  int m_blocks, n_tiles, n_chunks, tiles_per_chunk;
+  size_t off_s, off_m, off_c, off_v, off_i, bytes;
+};
+
+int check_fused(const gto_config *c, const void *hidden, int hidden_dim, const void *w) {
+  GTO_TRY(check_cfg(c, false));
+  if (c->dtype != GTO_BF16) return GTO_E_DTYPE;
+  if (c->k > kFusedMaxK || hidden_dim < 64 || hidden_dim % 64 != 0) return GTO_E_SHAPE;
+  GTO_TRY(check_logits(hidden));
+  GTO_TRY(check_logits(w));
+  return GTO_OK;
+}
+
+// Rows are processed in blocks of 256; the vocabulary (tiles of 256 tokens) is split into chunks
+// so that there are at least ~8 workgroups per compute unit.
+FusedPlan fused_plan(int64_t M, int V, int ktop) {
+  FusedPlan p{};
+  p.M = M;
+  p.m_blocks = (int)((M + 255) / 256);
+  p.n_tiles = (V + 255) / 256;
+  int nc = g_fused_chunks > 0 ? g_fused_chunks : (2048 + p.m_blocks - 1) / p.m_blocks;
+  if (nc > 64) nc = 64;
+  if (nc > p.n_tiles) nc = p.n_tiles;
+  if (nc < 1) nc = 1;
+  p.tiles_per_chunk = (p.n_tiles + nc - 1) / nc;
+  p.n_chunks = (p.n_tiles + p.tiles_per_chunk - 1) / p.tiles_per_chunk;
+  const size_t rows = (size_t)M * p.n_chunks;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  p.off_s = 0;
+  p.off_m = up(p.off_s + rows * sizeof(double));
+  p.off_c = up(p.off_m + rows * sizeof(float));
+  p.off_v = up(p.off_c + rows * sizeof(float));
+  p.off_i = up(p.off_v + rows * ktop * sizeof(float));
+  p.bytes = up(p.off_i + rows * ktop * sizeof(int32_t));
+  return p;
+}
+
+// Workspace of the fused calls: [partials of the row pass | gathered single logits].
+struct FusedWs {
+  size_t partial_bytes, off_slot, off_tok, off_out0, off_out1, bytes;
+};
+FusedWs fused_ws(const gto_config *c) {
+  FusedWs w{};
+  const int64_t M = (int64_t)c->R * rows_per_root(c);
+  size_t b = fused_plan(M, c->V, c->k).bytes;
+  const size_t b1 = fused_plan(M, c->V, 1).bytes;
+  w.partial_bytes = b1 > b ? b1 : b;
+  const size_t n = (size_t)c->R * (size_t)(c->g > c->d ? c->g : c->d);
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  w.off_slot = w.partial_bytes;
+  w.off_tok = up(w.off_slot + n * sizeof(int64_t));
+  w.off_out0 = up(w.off_tok + n * sizeof(int32_t));
+  w.off_out1 = up(w.off_out0 + n * sizeof(float));
+  w.bytes = up(w.off_out1 + n * sizeof(float));
+  // the backward pass lays the same memory out differently
+  const size_t rd = (size_t)c->R * c->d;
+  const size_t bwd = fused_plan((int64_t)rd, c->V, 1).bytes + 2 * up(rd * sizeof(int32_t)) + 256;
+  if (bwd > w.bytes) w.bytes = bwd;
+  return w;
+}
+
+int check_ws(const void *ws, size_t ws_bytes, size_t need) {
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255)) return GTO_E_WORKSPACE;
+  return GTO_OK;
+}
+
+// single logits hidden[slot] . w[tok] for the kept nodes (mode 0) or the path steps (mode 1)
+void run_gather(const gto_config *c, const gto_tree *t, const gto_reward *path, int mode, const void *hidden,
+                int hidden_dim, const void *w, void *ws, const FusedWs &L, float *out, hipStream_t st) {
+  char *base = static_cast<char *>(ws);
+  gto::PairArgs pa{};
+  pa.R = c->R; pa.d = c->d; pa.k = c->k; pa.g = c->g;
+  pa.sel_tok = t->sel_tok; pa.sel_depth = t->sel_depth; pa.sel_pslot = t->sel_pslot; pa.n_sel = t->n_sel;
+  pa.path_slot = path ? path->path_slot : nullptr; pa.path_node = path ? path->path_node : nullptr;
+  pa.slot = reinterpret_cast<int64_t *>(base + L.off_slot);
+  pa.tok = reinterpret_cast<int32_t *>(base + L.off_tok);
+  gto::GatherDotArgs ga{};
+  ga.hidden = hidden; ga.w = w; ga.hidden_dim = hidden_dim;
+  ga.n = (int64_t)c->R * (mode == 0 ? c->g : c->d);
+  ga.slot = pa.slot; ga.tok = pa.tok; ga.out = out;
+  ProfScope ps(mode == 0 ? "gather_nodes" : "gather_path", st);
+  gto::launch_pairs(pa, mode, st);
+  gto::launch_gather_dot(ga, st);
+}
+
+int run_fused_rows(const gto_config *c, const void *hidden, int hidden_dim, const void *w, int ktop,
+                   const int32_t *row_list, int64_t n_list, int out_by_list, float *row_max, float *row_lse,
+                   int32_t *top_tok, float *top_logp, float *top_logit, void *ws, size_t ws_bytes,
+                   const char *name, hipStream_t st) {
+  const int64_t M = row_list ? n_list : (int64_t)c->R * rows_per_root(c);
+  const FusedPlan p = fused_plan(M, c->V, ktop);
+  if (!ws || ws_bytes < p.bytes || (reinterpret_cast<uintptr_t>(ws) & 255)) return GTO_E_WORKSPACE;
+  char *base = static_cast<char *>(ws);
+  gto::FusedArgs a{};
+  a.hidden = hidden; a.w = w; a.hidden_dim = hidden_dim; a.V = c->V; a.rho = rows_per_root(c); a.d = c->d;
+  a.kslots = c->k; a.ktop = ktop; a.M = M; a.row_list = row_list; a.out_by_list = out_by_list;
+  a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
+  a.xcd_patches = g_fused_patches;
+  a.part_s = reinterpret_cast<double *>(base + p.off_s);
+  a.part_m = reinterpret_cast<float *>(base + p.off_m);
+  a.part_c = reinterpret_cast<float *>(base + p.off_c);
+  a.part_v = reinterpret_cast<float *>(base + p.off_v);
+  a.part_i = reinterpret_cast<int32_t *>(base + p.off_i);
+  a.row_max = row_max; a.row_lse = row_lse; a.top_tok = top_tok; a.top_logp = top_logp; a.top_logit = top_logit;
+  {
+    ProfScope ps(name, st);
+    gto::launch_fused_rows(a, st);
+  }
+  {
+    ProfScope ps("fused_merge", st);
+    gto::launch_fused_merge(a, st);
+  }
+  return GTO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -371,6 +493,168 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur, const
     gto::launch_ppo_bwd(a, cfg->dtype, cfg->R * cfg->d, (hipStream_t)hip_stream);
   }
   return hip_status();
+}
+
+int gto_fused_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out) {
+  if (!bytes_out) return GTO_E_NULL;
+  GTO_TRY(check_cfg(cfg, false));
+  if (cfg->k > kFusedMaxK || hidden_dim < 64 || hidden_dim % 64 != 0) return GTO_E_SHAPE;
+  *bytes_out = fused_ws(cfg).bytes;
+  return GTO_OK;
+}
+
+int gto_fused_draft_row_stats(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_vh,
+                              const gto_draft_stats *stats_out, float *top_logit_or_null, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_vh));
+  GTO_TRY(check_draft_stats(stats_out));
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, cfg->k, nullptr, 0, 0, stats_out->row_max,
+                         stats_out->row_lse, stats_out->top_tok, stats_out->top_logp, top_logit_or_null,
+                         workspace, workspace_bytes, "fused_rows_draft", (hipStream_t)hip_stream));
+  return hip_status();
+}
+
+int gto_fused_target_row_stats(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_vh,
+                               const gto_target_stats *stats_out, void *workspace, size_t workspace_bytes,
+                               void *hip_stream) {
+  GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_vh));
+  GTO_TRY(check_target_stats(stats_out));
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, 1, nullptr, 0, 0, stats_out->t_max, stats_out->t_lse,
+                         stats_out->t_argmax, nullptr, nullptr, workspace, workspace_bytes, "fused_rows_target",
+                         (hipStream_t)hip_stream));
+  return hip_status();
+}
+
+int gto_expand_tree_fused(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_draft_vh,
+                          const gto_draft_stats *stats_out, const gto_pool *pool_out, void *workspace,
+                          size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_draft_vh));
+  GTO_TRY(check_draft_stats(stats_out));
+  GTO_TRY(check_pool(pool_out));
+  GTO_TRY(check_ws(workspace, workspace_bytes, fused_ws(cfg).bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_draft_vh, cfg->k, nullptr, 0, 0, stats_out->row_max,
+                         stats_out->row_lse, stats_out->top_tok, stats_out->top_logp, nullptr, workspace,
+                         workspace_bytes, "fused_rows_draft", st));
+  run_expand(cfg, stats_out, pool_out, st);
+  return hip_status();
+}
+
+int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const void *hidden, int32_t hidden_dim,
+                          const void *w_target_vh, const gto_target_stats *stats_out,
+                          const gto_reward *reward_out, void *workspace, size_t workspace_bytes,
+                          void *hip_stream) {
+  GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_target_vh));
+  GTO_TRY(check_tree(tree));
+  GTO_TRY(check_target_stats(stats_out));
+  GTO_TRY(check_reward(reward_out));
+  const FusedWs L = fused_ws(cfg);
+  GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_target_vh, 1, nullptr, 0, 0, stats_out->t_max,
+                         stats_out->t_lse, stats_out->t_argmax, nullptr, nullptr, workspace, workspace_bytes,
+                         "fused_rows_target", st));
+  float *node_logit = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_out0);
+  run_gather(cfg, tree, nullptr, 0, hidden, hidden_dim, w_target_vh, workspace, L, node_logit, st);
+  {
+    gto::RewardArgs a{};
+    a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.dtype = cfg->dtype; a.reward_mode = cfg->reward_mode;
+    a.row_stride = 0; a.eta = cfg->eta;
+    a.target_logits = nullptr; a.node_logit = node_logit; a.t_lse = stats_out->t_lse; a.t_argmax = stats_out->t_argmax;
+    a.sel_tok = tree->sel_tok; a.sel_parent = tree->sel_parent; a.sel_depth = tree->sel_depth;
+    a.sel_pslot = tree->sel_pslot; a.sel_slot = tree->sel_slot; a.sel_leaf = tree->sel_leaf; a.n_sel = tree->n_sel;
+    a.node_q = reward_out->node_q; a.node_cum = reward_out->node_cum; a.reward = reward_out->reward;
+    a.reward_aux = reward_out->reward_aux; a.n_leaves = reward_out->n_leaves; a.path_len = reward_out->path_len;
+    a.path_node = reward_out->path_node; a.path_slot = reward_out->path_slot;
+    ProfScope ps("reward_path", st);
+    gto::launch_reward(a, st);
+  }
+  return hip_status();
+}
+
+int gto_ppo_surrogate_fwd_fused(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                const void *hidden_cur, const void *hidden_ref_on_cur, int32_t hidden_dim,
+                                const void *w_draft_vh, const gto_draft_stats *draft_stats_cur,
+                                const gto_draft_stats *ref_stats, const float *adv, const gto_ppo *out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, true));
+  GTO_TRY(check_fused(cfg, hidden_cur, hidden_dim, w_draft_vh));
+  GTO_TRY(check_logits(hidden_ref_on_cur));
+  GTO_TRY(check_tree(tree_cur));
+  GTO_TRY(check_reward(path_cur));
+  if (!draft_stats_cur || !draft_stats_cur->row_lse || !ref_stats || !ref_stats->row_lse || !adv) return GTO_E_NULL;
+  GTO_TRY(check_ppo(out));
+  const FusedWs L = fused_ws(cfg);
+  GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  float *lc = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_out0);
+  float *lr = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_out1);
+  run_gather(cfg, tree_cur, path_cur, 1, hidden_cur, hidden_dim, w_draft_vh, workspace, L, lc, st);
+  run_gather(cfg, tree_cur, path_cur, 1, hidden_ref_on_cur, hidden_dim, w_draft_vh, workspace, L, lr, st);
+  gto::PpoFwdArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.m = cfg->group_size; a.dtype = cfg->dtype;
+  a.row_stride = 0; a.eps = cfg->eps; a.grad_scale = cfg->grad_scale;
+  a.draft_logits = nullptr; a.ref_logits = nullptr; a.path_logit_cur = lc; a.path_logit_ref = lr;
+  a.draft_lse = draft_stats_cur->row_lse; a.ref_lse = ref_stats->row_lse; a.ref_lse_by_step = 0;
+  a.sel_tok = tree_cur->sel_tok; a.path_len = path_cur->path_len; a.path_node = path_cur->path_node;
+  a.path_slot = path_cur->path_slot; a.adv = adv;
+  a.logM = out->logM; a.logM0 = out->logM0; a.ratio = out->ratio; a.term = out->term; a.coef = out->coef;
+  a.loss_group = out->loss_group; a.loss = out->loss; a.active = out->active;
+  {
+    ProfScope ps("ppo_fwd", st);
+    gto::launch_ppo_fwd(a, st);
+  }
+  return hip_status();
+}
+
+int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                const gto_ppo *fwd, const void *hidden_cur, int32_t hidden_dim,
+                                const void *w_draft_vh, const gto_draft_stats *draft_stats_cur, float *grad_rows,
+                                int32_t *grad_slot, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, true));
+  GTO_TRY(check_fused(cfg, hidden_cur, hidden_dim, w_draft_vh));
+  GTO_TRY(check_tree(tree_cur));
+  GTO_TRY(check_reward(path_cur));
+  GTO_TRY(check_ppo(fwd));
+  if (!draft_stats_cur || !draft_stats_cur->row_lse || !grad_rows || !grad_slot) return GTO_E_NULL;
+  GTO_TRY(check_ws(workspace, workspace_bytes, fused_ws(cfg).bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t rd = (int64_t)cfg->R * cfg->d;
+  const FusedPlan p = fused_plan(rd, cfg->V, 1);
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  char *base = static_cast<char *>(workspace);
+  int32_t *list_p = reinterpret_cast<int32_t *>(base + p.bytes);
+  int32_t *list_slot = reinterpret_cast<int32_t *>(base + p.bytes + up(rd * sizeof(int32_t)));
+  int32_t *count = reinterpret_cast<int32_t *>(base + p.bytes + 2 * up(rd * sizeof(int32_t)));
+  {
+    gto::BwdRowsArgs b{};
+    b.R = cfg->R; b.d = cfg->d; b.k = cfg->k;
+    b.path_slot = path_cur->path_slot; b.coef = fwd->coef;
+    b.grad_slot = grad_slot; b.list_p = list_p; b.list_slot = list_slot; b.count = count;
+    ProfScope ps("bwd_rows", st);
+    gto::launch_bwd_rows(b, st);
+    if (cfg->flags & GTO_FLAG_GRAD_ZERO_FILL) gto::launch_zero_rows(grad_rows, grad_slot, (int)rd, cfg->V, st);
+  }
+  gto::FusedArgs a{};
+  a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
+  a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
+  a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
+  a.xcd_patches = g_fused_patches;
+  a.part_s = reinterpret_cast<double *>(base + p.off_s);
+  a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
+  a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g; a.grad_rows = grad_rows;
+  {
+    ProfScope ps("fused_rows_bwd", st);
+    gto::launch_fused_rows(a, st);
+    gto::launch_fused_bwd_fixup(a, st);
+  }
+  return hip_status();
+}
+
+int gto_set_fused_tuning(int n_chunks, int xcd_patches) {
+  g_fused_chunks = n_chunks > 0 ? n_chunks : 0;
+  g_fused_patches = xcd_patches ? 1 : 0;
+  return GTO_OK;
 }
 
 int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {

@@ -1,0 +1,528 @@
+// Fused LM-head variant: logits = hidden . W^T are produced tile by tile on the matrix cores and
+// reduced to the row statistics (max, log-sum-exp, exact top-k) in the epilogue, so the logits
+// never reach HBM.
+//
+//  k_fused_rows  : 256 x 256 output tile per workgroup iteration (4 waves, each 128 x 128 as 4 x 4
+//                  MFMA 32x32x16 bf16 tiles, fp32 accumulators), K-slabs of 64 double-buffered in
+//                  LDS.  A workgroup owns 256 rows and sweeps a chunk of the vocabulary; after each
+//                  tile the accumulators are staged through LDS so that thread t owns row t and
+//                  folds its 256 new logits into its running (max, sum, top-k list) in registers.
+//  k_fused_merge : combines the per-chunk partials of a row into the final statistics.
+//  k_gather_dot  : single logits (hidden row . W row) for the few (row, token) pairs the reward
+//                  and the surrogate need.
+#include "gto_device.h"
+#include "gto_kernels.h"
+
+#ifndef GTO_FUSED_PITCH_PAD
+#define GTO_FUSED_PITCH_PAD 0   // experiments only: extra elements between rows of hidden and W
+#endif
+#ifndef GTO_FUSED_EXP
+#define GTO_FUSED_EXP 0   // experiments only: 1 = no global loads in the main loop, 2 = one MFMA per k step
+#endif
+
+namespace gto {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int FBM = 256, FBN = 256, FBK = 64;
+constexpr int FLD = FBK + 8;                       // padded LDS row (elements): 144 bytes
+constexpr int FSTAGE = (FBM + FBN) * FLD;          // elements per stage
+constexpr int FKT = 16;                            // capacity of the per-thread top list
+constexpr int FSTG_LD = 65;                        // staging row stride (floats)
+constexpr size_t kFusedLdsBytes = (size_t)2 * FSTAGE * sizeof(uint16_t);
+
+// index of the statistics entry (= logits slot) of the q-th used row of root r
+__device__ __forceinline__ int64_t used_slot_index(int64_t gidx, int rho, int d, int k) {
+  const int64_t r = gidx / rho;
+  const int q = (int)(gidx - r * rho);
+  return r * d * k + (q ? k + q - 1 : 0);
+}
+
+template <int KT>
+struct RowState {
+  float m, c;
+  double s;
+  float v[KT];
+  int id[KT];
+};
+
+template <int KT>
+__device__ __forceinline__ void list_insert(float (&v)[KT], int (&id)[KT], float x, int xi) {
+  // v/id sorted best first; branch-free shift-insert
+  bool prev = false;   // "x beats entry i-1"
+  float pv = 0.f;
+  int pi = 0;
+#pragma unroll
+  for (int i = 0; i < KT; ++i) {
+    const bool b = better(x, xi, v[i], id[i]);
+    const float cv = v[i];
+    const int ci = id[i];
+    v[i] = b ? (prev ? pv : x) : cv;
+    id[i] = b ? (prev ? pi : xi) : ci;
+    prev = b;
+    pv = cv;
+    pi = ci;
+  }
+}
+
+enum FusedMode { kFusedStats = 0, kFusedBwd = 1 };
+
+template <int KT, int MODE>
+__global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
+  extern __shared__ __align__(16) uint16_t lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // workgroup -> (row block, vocabulary chunk)
+  int mblock, chunk;
+  {
+    const int id = blockIdx.x;
+    if (a.xcd_patches) {
+      // 32 consecutive workgroups of one XCD form a 4 (row blocks) x 8 (chunks) patch, so that the
+      // XCD's L2 serves 4 A streams and 8 W streams to 32 workgroups
+      const int xcd = id & 7, seq = id >> 3;
+      const int patch = (seq >> 5) * 8 + xcd, within = seq & 31;
+      const int pcs = (a.n_chunks + 7) >> 3;
+      mblock = (patch / pcs) * 4 + (within >> 3);
+      chunk = (patch % pcs) * 8 + (within & 7);
+    } else {
+      mblock = id / a.n_chunks;
+      chunk = id - mblock * a.n_chunks;
+    }
+    if (mblock >= a.m_blocks || chunk >= a.n_chunks) return;
+  }
+  const int tile0 = chunk * a.tiles_per_chunk;
+  const int tile1 = min(tile0 + a.tiles_per_chunk, a.n_tiles);
+  if (tile0 >= tile1) return;
+  const int64_t row0 = (int64_t)mblock * FBM;
+  const int64_t M = a.m_dev ? min((int64_t)*a.m_dev, a.M) : a.M;   // row count may live on the device
+  if (row0 >= M) return;
+  const int HD = a.hidden_dim;
+  const int kt_count = HD / FBK;
+  const uint16_t *__restrict__ Hp = static_cast<const uint16_t *>(a.hidden);
+  const uint16_t *__restrict__ Wp = static_cast<const uint16_t *>(a.w);
+
+  // global -> LDS copy assignment: 8 chunks of 16 bytes per operand per thread
+  const int ld_row = tid >> 3, ld_kc = tid & 7;          // rows ld_row + 32 i, i = 0..7
+  int64_t a_off[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int64_t g = row0 + ld_row + 32 * i;
+    if (g >= M) g = M - 1;
+    const int64_t slot = a.row_list ? (int64_t)a.row_list[g] : used_slot_index(g, a.rho, a.d, a.kslots);
+    a_off[i] = slot * (HD + GTO_FUSED_PITCH_PAD) + ld_kc * 8;
+  }
+
+  // the list keeps the KT >= ktop best of the row; its last entry is the insertion threshold
+  RowState<KT> st;
+  st.m = neg_inf(); st.c = 0.f; st.s = 0.0;
+#pragma unroll
+  for (int i = 0; i < KT; ++i) { st.v[i] = neg_inf(); st.id[i] = kNoId; }
+  const int ktop = a.ktop;
+  // backward mode: thread t writes coef * (-softmax) of row t and sums the probabilities of all
+  // tokens but the accepted one
+  float b_lse = 0.f, b_coef = 0.f;
+  int b_tok = -1;
+  float *b_out = nullptr;
+  double b_others = 0.0;
+  if (MODE == kFusedBwd) {
+    const int64_t gme = row0 + tid;
+    if (gme < M) {
+      const int pidx = a.list_p[gme];
+      const int rr = pidx / a.d;
+      b_lse = a.lse_by_slot[a.row_list[gme]];
+      b_coef = a.coef[rr];
+      b_tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+      b_out = a.grad_rows + (int64_t)pidx * a.V;
+    }
+  }
+
+  for (int tile = tile0; tile < tile1; ++tile) {
+    const int n0 = tile * FBN;
+    int64_t b_off[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int n = n0 + ld_row + 32 * i;
+      if (n >= a.V) n = a.V - 1;
+      b_off[i] = (int64_t)n * (HD + GTO_FUSED_PITCH_PAD) + ld_kc * 8;
+    }
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    u32x4 ra[8], rb[8];
+    // prologue: slab 0 -> stage 0
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      ra[i] = *reinterpret_cast<const u32x4 *>(Hp + a_off[i]);
+      rb[i] = *reinterpret_cast<const u32x4 *>(Wp + b_off[i]);
+    }
+    __syncthreads();   // previous tile's epilogue no longer reads the staging area
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<u32x4 *>(lds + (ld_row + 32 * i) * FLD + ld_kc * 8) = ra[i];
+      *reinterpret_cast<u32x4 *>(lds + (FBM + ld_row + 32 * i) * FLD + ld_kc * 8) = rb[i];
+    }
+    __syncthreads();
+
+    // Fragment addresses of this lane inside a stage (elements): row (lane & 31) of each 32-row
+    // tile, 8 consecutive k starting at 8 * (lane >> 5) within each 16-wide k step.
+    const int fa_base = (wm * 128 + (lane & 31)) * FLD + (lane >> 5) * 8;
+    const int fb_base = (FBM + wn * 128 + (lane & 31)) * FLD + (lane >> 5) * 8;
+    bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      fa[0][t] = *reinterpret_cast<const bf16x8 *>(lds + fa_base + t * 32 * FLD);
+      fb[0][t] = *reinterpret_cast<const bf16x8 *>(lds + fb_base + t * 32 * FLD);
+    }
+    for (int kt = 0; kt < kt_count; ++kt) {
+      const int cur = kt & 1;
+      const uint16_t *sS = lds + cur * FSTAGE;
+      const bool more = (kt + 1 < kt_count);
+#if GTO_FUSED_EXP != 1
+      if (more) {
+        const int k1 = (kt + 1) * FBK;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          ra[i] = *reinterpret_cast<const u32x4 *>(Hp + a_off[i] + k1);
+          rb[i] = *reinterpret_cast<const u32x4 *>(Wp + b_off[i] + k1);
+        }
+      }
+#endif
+      // software pipeline over the four 16-wide k steps of the slab: the fragments of step kk+1
+      // are read from LDS while the 16 MFMAs of step kk run
+#pragma unroll
+      for (int kk = 0; kk < FBK / 16; ++kk) {
+        const int cb = kk & 1, nb = cb ^ 1;
+        if (kk + 1 < FBK / 16) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            fa[nb][t] = *reinterpret_cast<const bf16x8 *>(sS + fa_base + t * 32 * FLD + (kk + 1) * 16);
+            fb[nb][t] = *reinterpret_cast<const bf16x8 *>(sS + fb_base + t * 32 * FLD + (kk + 1) * 16);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the MFMAs they overlap with
+#if GTO_FUSED_EXP == 2
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][0] + fa[cb][1] + fa[cb][2] + fa[cb][3],
+                                                            fb[cb][0] + fb[cb][1] + fb[cb][2] + fb[cb][3],
+                                                            acc[0][0], 0, 0, 0);
+#else
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (more) {
+        uint16_t *dS = lds + (cur ^ 1) * FSTAGE;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          *reinterpret_cast<u32x4 *>(dS + (ld_row + 32 * i) * FLD + ld_kc * 8) = ra[i];
+          *reinterpret_cast<u32x4 *>(dS + (FBM + ld_row + 32 * i) * FLD + ld_kc * 8) = rb[i];
+        }
+      }
+      __syncthreads();
+      if (more) {
+        const uint16_t *nS = lds + (cur ^ 1) * FSTAGE;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          fa[0][t] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + t * 32 * FLD);
+          fb[0][t] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + t * 32 * FLD);
+        }
+      }
+    }
+
+    // ---- epilogue: four 64-column quarters through the staging area; thread t owns row t
+    float *stg = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      if (wn == (qd >> 1)) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int n2 = 0; n2 < 2; ++n2)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int row = wm * 128 + mt * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+              const int col = n2 * 32 + (lane & 31);
+              stg[row * FSTG_LD + col] = acc[mt][(qd & 1) * 2 + n2][e];
+            }
+      }
+      __syncthreads();
+      {
+        const float *mine = stg + tid * FSTG_LD;
+        const int cbase = n0 + qd * 64;
+        const int ncols = min(64, a.V - cbase);     // <= 0 for quarters beyond the vocabulary
+        if (MODE == kFusedBwd) {
+          if (ncols > 0 && b_out != nullptr) {
+            float part = 0.f;
+            const bool vec = ((a.V & 3) == 0) && (ncols == 64);
+            for (int c4 = 0; c4 < ncols; c4 += 4) {
+              float gq[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int c2 = c4 + e;
+                const float x = (c2 < ncols) ? mine[c2] : neg_inf();
+                const float pv = __builtin_amdgcn_exp2f((x - b_lse) * kLog2e);
+                part += (cbase + c2 == b_tok) ? 0.f : pv;
+                gq[e] = -b_coef * pv;
+              }
+              if (vec) {
+                const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
+                __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(b_out + cbase + c4));
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  if (c4 + e < ncols) b_out[cbase + c4 + e] = gq[e];
+              }
+            }
+            b_others += (double)part;
+          }
+        } else
+        if (ncols > 0) {
+          float cm = neg_inf();
+          for (int c2 = 0; c2 < ncols; ++c2) cm = fmaxf(cm, mine[c2]);
+          const float m_new = fmaxf(st.m, cm);
+          const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
+          const float scale = __builtin_amdgcn_exp2f(st.c - c_new);
+          double s = (st.m == neg_inf()) ? 0.0 : st.s * (double)scale;
+          float p = 0.f;
+          const float thr_v = st.v[KT - 1];
+          bool any_hit = false;
+          for (int c2 = 0; c2 < ncols; ++c2) {
+            const float x = mine[c2];
+            p += __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, -c_new));
+            any_hit = any_hit || (x > thr_v) || (st.id[KT - 1] == kNoId);
+          }
+          st.s = s + (double)p;
+          st.m = m_new;
+          st.c = c_new;
+          if (any_hit) {
+            for (int c2 = 0; c2 < ncols; ++c2) {
+              const float x = mine[c2];
+              const int xi = cbase + c2;
+              if (better(x, xi, st.v[KT - 1], st.id[KT - 1])) list_insert<KT>(st.v, st.id, x, xi);
+            }
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- partial results of this (row, chunk)
+  const int64_t g = row0 + tid;
+  if (MODE == kFusedBwd) {
+    if (g < M) a.part_s[g * a.n_chunks + chunk] = b_others;
+    return;
+  }
+  if (g < M) {
+    const int64_t pi = g * a.n_chunks + chunk;
+    a.part_m[pi] = st.m;
+    a.part_c[pi] = st.c;
+    a.part_s[pi] = st.s;
+#pragma unroll
+    for (int i = 0; i < KT; ++i) {
+      if (i < ktop) {
+        a.part_v[pi * ktop + i] = st.v[i];
+        a.part_i[pi * ktop + i] = st.id[i];
+      }
+    }
+  }
+}
+
+// One wave per row: merge the chunk partials into the final statistics.
+__global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
+  const int64_t g = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int nc = a.n_chunks, ktop = a.ktop;
+  const int64_t oi = a.row_list ? (a.out_by_list ? g : (int64_t)a.row_list[g])
+                                : used_slot_index(g, a.rho, a.d, a.kslots);
+  __shared__ float s_v[64 * FKT];
+  __shared__ int s_i[64 * FKT];
+  float m = neg_inf(), c = neg_inf();
+  double s = 0.0;
+  if (lane < nc) {
+    m = a.part_m[g * nc + lane];
+    if (m != neg_inf()) {
+      c = a.part_c[g * nc + lane];
+      s = a.part_s[g * nc + lane];
+    }
+  }
+  const float M = wave_max(m);
+  const float C = wave_max(c);
+  const double S = wave_sum((m == neg_inf()) ? 0.0 : s * (double)__builtin_amdgcn_exp2f(c - C));
+  const double lse = (double)M + kLn2 * (((double)C - (double)M * (double)kLog2e) + log2(S));
+  if (lane == 0) {
+    if (a.row_max) a.row_max[oi] = M;
+    a.row_lse[oi] = (float)lse;
+  }
+  if (a.top_tok == nullptr) return;
+  const int total = nc * ktop;
+  for (int j = lane; j < total; j += 64) {
+    s_v[j] = a.part_v[g * total + j];
+    s_i[j] = a.part_i[g * total + j];
+  }
+  __syncthreads();
+  for (int j = lane; j < total; j += 64) {
+    const float v = s_v[j];
+    const int id = s_i[j];
+    if (id == kNoId) continue;
+    int rank = 0;
+    for (int u = 0; u < total; ++u) rank += better(s_v[u], s_i[u], v, id) ? 1 : 0;
+    if (rank < ktop) {
+      a.top_tok[oi * ktop + rank] = id;
+      if (a.top_logp) a.top_logp[oi * ktop + rank] = fminf((float)((double)v - lse), 0.f);
+      if (a.top_logit) a.top_logit[oi * ktop + rank] = v;
+    }
+  }
+}
+
+// Backward fix-up, one thread per processed row: the accepted token's entry is coef times the sum
+// of all other probabilities (summed over the vocabulary chunks in a fixed order).
+__global__ void k_fused_bwd_fixup(FusedArgs a) {
+  const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t M = a.m_dev ? min((int64_t)*a.m_dev, a.M) : a.M;
+  if (g >= M) return;
+  double tot = 0.0;
+  for (int c = 0; c < a.n_chunks; ++c) tot += a.part_s[g * a.n_chunks + c];
+  const int pidx = a.list_p[g];
+  const int rr = pidx / a.d;
+  const int tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+  a.grad_rows[(int64_t)pidx * a.V + tok] = (float)((double)a.coef[rr] * tot);
+}
+
+// Ordered compaction (single workgroup): the (root, step) pairs that carry a gradient, their
+// hidden-row slots, and grad_slot for every pair.
+__global__ __launch_bounds__(1024) void k_bwd_rows(BwdRowsArgs a) {
+  __shared__ int s_wave[16];
+  __shared__ int s_base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_base = 0;
+  __syncthreads();
+  const int n = a.R * a.d;
+  for (int p0 = 0; p0 < n; p0 += 1024) {
+    const int p = p0 + tid;
+    bool valid = false;
+    int j = -1;
+    if (p < n) {
+      j = a.path_slot[p];
+      valid = (j >= 0) && (a.coef[p / a.d] != 0.f);
+      a.grad_slot[p] = valid ? j : -1;
+    }
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(valid);
+    const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wave[wave] = __builtin_popcountll(bal);
+    __syncthreads();
+    int off = s_base;
+    for (int w = 0; w < wave; ++w) off += s_wave[w];
+    if (valid) {
+      const int r = p / a.d, t = p - r * a.d;
+      a.list_p[off + before] = p;
+      a.list_slot[off + before] = (int)stat_index(r, t, j, a.d, a.k);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int w = 0; w < 16; ++w) tot += s_wave[w];
+      s_base += tot;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) *a.count = s_base;
+}
+
+__global__ void k_zero_rows(float *grad_rows, const int32_t *grad_slot, int V) {
+  if (grad_slot[blockIdx.x] >= 0) return;
+  float *o = grad_rows + (int64_t)blockIdx.x * V;
+  for (int i = threadIdx.x; i < V; i += blockDim.x) o[i] = 0.f;
+}
+
+// One wave per (row slot, token): fp32 dot product of a hidden row and a W row.
+__global__ __launch_bounds__(64) void k_gather_dot(GatherDotArgs a) {
+  const int64_t p = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int64_t slot = a.slot[p];
+  const int tok = a.tok[p];
+  if (slot < 0 || tok < 0) {
+    if (lane == 0) a.out[p] = 0.f;
+    return;
+  }
+  const uint16_t *h = static_cast<const uint16_t *>(a.hidden) + slot * a.hidden_dim;
+  const uint16_t *w = static_cast<const uint16_t *>(a.w) + (int64_t)tok * a.hidden_dim;
+  float acc = 0.f;
+  for (int e0 = lane * 8; e0 < a.hidden_dim; e0 += 64 * 8) {
+    const u32x4 hq = *reinterpret_cast<const u32x4 *>(h + e0);
+    const u32x4 wq = *reinterpret_cast<const u32x4 *>(w + e0);
+    float hx[8], wx[8];
+    Elem<uint16_t>::unpack(hq, hx);
+    Elem<uint16_t>::unpack(wq, wx);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(hx[e], wx[e], acc);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+  if (lane == 0) a.out[p] = acc;
+}
+
+template <typename K>
+static void set_lds_attr(K kern) {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kFusedLdsBytes);
+}
+
+static int fused_grid(const FusedArgs &a) {
+  if (!a.xcd_patches) return a.m_blocks * a.n_chunks;
+  const int pms = (a.m_blocks + 3) / 4, pcs = (a.n_chunks + 7) / 8;
+  return ((pms * pcs + 7) / 8) * 8 * 32;
+}
+
+void launch_fused_rows(const FusedArgs &a, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    set_lds_attr(k_fused_rows<1, kFusedStats>);
+    set_lds_attr(k_fused_rows<8, kFusedStats>);
+    set_lds_attr(k_fused_rows<16, kFusedStats>);
+    set_lds_attr(k_fused_rows<1, kFusedBwd>);
+    attr_set = true;
+  }
+  const int blocks = fused_grid(a);
+  if (a.grad_rows != nullptr)
+    hipLaunchKernelGGL((k_fused_rows<1, kFusedBwd>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+  else if (a.ktop <= 1)
+    hipLaunchKernelGGL((k_fused_rows<1, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+  else if (a.ktop <= 8)
+    hipLaunchKernelGGL((k_fused_rows<8, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+  else
+    hipLaunchKernelGGL((k_fused_rows<16, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+}
+
+void launch_fused_bwd_fixup(const FusedArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_fused_bwd_fixup, dim3((unsigned)((a.M + 255) / 256)), dim3(256), 0, st, a);
+}
+
+void launch_bwd_rows(const BwdRowsArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_bwd_rows, dim3(1), dim3(1024), 0, st, a);
+}
+
+void launch_zero_rows(float *grad_rows, const int32_t *grad_slot, int rows, int V, hipStream_t st) {
+  hipLaunchKernelGGL(k_zero_rows, dim3(rows), dim3(256), 0, st, grad_rows, grad_slot, V);
+}
+
+void launch_fused_merge(const FusedArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_fused_merge, dim3((unsigned)a.M), dim3(64), 0, st, a);
+}
+
+void launch_gather_dot(const GatherDotArgs &a, hipStream_t st) {
+  if (a.n > 0) hipLaunchKernelGGL(k_gather_dot, dim3((unsigned)a.n), dim3(64), 0, st, a);
+}
+
+}  // namespace gto

@@ -51,6 +51,7 @@ struct RewardArgs {
   int64_t row_stride;
   float eta;
   const void *target_logits;
+  const float *node_logit;   // optional [R, g]: logits of the kept tokens gathered beforehand (fused variant)
   const float *t_lse;
   const int32_t *t_argmax;
   const int32_t *sel_tok, *sel_parent, *sel_depth, *sel_pslot, *sel_slot, *sel_leaf, *n_sel;
@@ -70,6 +71,7 @@ struct PpoFwdArgs {
   int64_t row_stride;
   float eps, grad_scale;
   const void *draft_logits, *ref_logits;
+  const float *path_logit_cur, *path_logit_ref;   // optional [R, d]: gathered beforehand (fused variant)
   const float *draft_lse;   // [R, d, k]
   const float *ref_lse;     // [R, d, k] if ref_lse_by_step == 0, else [R, d]
   int ref_lse_by_step;
@@ -79,6 +81,59 @@ struct PpoFwdArgs {
   int32_t *active;
 };
 
+struct FusedArgs {
+  const void *hidden;        // bf16 [R, d, kslots, hidden_dim]
+  const void *w;             // bf16 [V, hidden_dim]
+  int hidden_dim, V, rho, d, kslots, ktop;
+  int64_t M;                 // rows processed (used slots, or capacity of row_list)
+  const int32_t *m_dev;      // optional: actual row count in device memory (<= M)
+  const int32_t *row_list;   // optional: slot index of each processed row
+  int out_by_list;           // with row_list: statistics are written at the list position, not at the slot
+  int m_blocks, n_tiles, n_chunks, tiles_per_chunk, xcd_patches;
+  float *part_m, *part_c;    // [M, n_chunks]
+  double *part_s;            // [M, n_chunks]
+  float *part_v;             // [M, n_chunks, ktop]
+  int32_t *part_i;           // [M, n_chunks, ktop]
+  float *row_max, *row_lse;  // final statistics (row_max may be null)
+  int32_t *top_tok;          // may be null
+  float *top_logp, *top_logit;  // may be null
+  // backward mode (grad_rows != null): rows come from row_list (hidden slots) / list_p ((root, step))
+  const int32_t *list_p, *sel_tok, *path_node;
+  const float *coef, *lse_by_slot;
+  int g;
+  float *grad_rows;          // [R, d, V]
+};
+
+struct BwdRowsArgs {
+  int R, d, k;
+  const int32_t *path_slot;
+  const float *coef;
+  int32_t *grad_slot, *list_p, *list_slot, *count;
+};
+
+struct GatherDotArgs {
+  const void *hidden, *w;
+  int hidden_dim;
+  int64_t n;
+  const int64_t *slot;       // [n] slot index of the hidden row, < 0: skip
+  const int32_t *tok;        // [n]
+  float *out;                // [n]
+};
+
+struct PairArgs {
+  int R, d, k, g;
+  const int32_t *sel_tok, *sel_depth, *sel_pslot, *n_sel;      // kept nodes (mode 0)
+  const int32_t *path_slot, *path_node;                       // path steps (mode 1)
+  int64_t *slot;
+  int32_t *tok;
+};
+void launch_pairs(const PairArgs &a, int mode, hipStream_t st);
+void launch_fused_rows(const FusedArgs &a, hipStream_t st);
+void launch_fused_bwd_fixup(const FusedArgs &a, hipStream_t st);
+void launch_bwd_rows(const BwdRowsArgs &a, hipStream_t st);
+void launch_zero_rows(float *grad_rows, const int32_t *grad_slot, int rows, int V, hipStream_t st);
+void launch_fused_merge(const FusedArgs &a, hipStream_t st);
+void launch_gather_dot(const GatherDotArgs &a, hipStream_t st);
 void set_waves_per_row(int w);
 int get_waves_per_row();
 void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st);

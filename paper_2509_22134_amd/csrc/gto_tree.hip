@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
     const int js = a.sel_pslot[sel0 + i];
     const int tok = a.sel_tok[sel0 + i];
     const int64_t si = stat_index(r, lvl, js, d, k);
-    const float x = Elem<T>::load1(logits + si * a.row_stride + tok);
+    const float x = a.node_logit ? a.node_logit[sel0 + i] : Elem<T>::load1(logits + si * a.row_stride + tok);
     s_logt[i] = (double)x - (double)a.t_lse[si];
     s_parent[i] = a.sel_parent[sel0 + i];
   }
@@ -325,9 +325,11 @@ __global__ void k_ppo_root(PpoFwdArgs a) {
     const int j = a.path_slot[rt];
     const int tok = a.sel_tok[(int64_t)r * a.g + a.path_node[rt]];
     const int64_t si = stat_index(r, t, j, d, k);
-    lm += (double)Elem<T>::load1(dl + si * a.row_stride + tok) - (double)a.draft_lse[si];
+    const float xc = a.path_logit_cur ? a.path_logit_cur[rt] : Elem<T>::load1(dl + si * a.row_stride + tok);
+    lm += (double)xc - (double)a.draft_lse[si];
     const double rlse = a.ref_lse_by_step ? (double)a.ref_lse[rt] : (double)a.ref_lse[si];
-    lm0 += (double)Elem<T>::load1(rl + si * a.row_stride + tok) - rlse;
+    const float xr = a.path_logit_ref ? a.path_logit_ref[rt] : Elem<T>::load1(rl + si * a.row_stride + tok);
+    lm0 += (double)xr - rlse;
   }
   const int lden = (l > 1) ? l : 1;
   const double s = exp((lm - lm0) / lden);
@@ -365,6 +367,35 @@ __global__ __launch_bounds__(256) void k_ppo_loss(PpoFwdArgs a) {
     __syncthreads();
   }
   if (threadIdx.x == 0) a.loss[0] = (float)(s_red[0] / K);
+}
+
+// (slot, token) pairs whose single logits the fused variant computes as dot products
+__global__ void k_pairs(PairArgs a, int mode) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per = (mode == 0) ? a.g : a.d;
+  if (p >= (int64_t)a.R * per) return;
+  const int r = (int)(p / per), i = (int)(p - (int64_t)r * per);
+  int64_t slot = -1;
+  int tok = -1;
+  if (mode == 0) {
+    if (i < a.n_sel[r]) {
+      slot = stat_index(r, a.sel_depth[p] - 1, a.sel_pslot[p], a.d, a.k);
+      tok = a.sel_tok[p];
+    }
+  } else {
+    const int j = a.path_slot[p];
+    if (j >= 0) {
+      slot = stat_index(r, i, j, a.d, a.k);
+      tok = a.sel_tok[(int64_t)r * a.g + a.path_node[p]];
+    }
+  }
+  a.slot[p] = slot;
+  a.tok[p] = tok;
+}
+
+void launch_pairs(const PairArgs &a, int mode, hipStream_t st) {
+  const int64_t n = (int64_t)a.R * ((mode == 0) ? a.g : a.d);
+  hipLaunchKernelGGL(k_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a, mode);
 }
 
 void launch_ppo_fwd(const PpoFwdArgs &a, hipStream_t st) {

@@ -58,3 +58,44 @@ class GtoPath:
         if self.want_grad:
             B.gto_ppo_surrogate_bwd(self.cfg, cur["tree"], cur["reward"], self.ppo, D_cur, cur["dstats"],
                                     self.grad_rows, self.grad_slot)
+
+
+class GtoFusedPath:
+    """The same step with the logits produced on the fly from hidden states and LM heads
+    (draft head for both draft models, target head for the target)."""
+
+    def __init__(self, *, R, d, k, g, V, hidden, group_size, device, eta=1.0, eps=0.2, delta=1e-6,
+                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True):
+        self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=B.GTO_BF16, group_size=group_size,
+                                 reward_mode=reward_mode, eta=eta, eps=eps, delta=delta, grad_scale=grad_scale,
+                                 flags=flags)
+        self.hidden = hidden
+        self.want_grad = want_grad
+        self.buf = {}
+        for tag in ("cur", "ref"):
+            self.buf[tag] = dict(dstats=B.alloc_draft_stats(self.cfg, device), pool=B.alloc_pool(self.cfg, device),
+                                 tree=B.alloc_tree(self.cfg, device), tstats=B.alloc_target_stats(self.cfg, device),
+                                 reward=B.alloc_reward(self.cfg, device))
+        self.adv = torch.empty((R,), dtype=torch.float32, device=device)
+        self.ppo = B.alloc_ppo(self.cfg, device)
+        self.workspace = torch.empty((B.gto_fused_workspace_bytes(self.cfg, hidden),), dtype=torch.uint8, device=device)
+        if want_grad:
+            self.grad_rows = torch.empty((R, d, V), dtype=torch.float32, device=device)
+            self.grad_slot = torch.empty((R, d), dtype=torch.int32, device=device)
+
+    def build_and_score(self, tag, H, W_draft, W_target):
+        b = self.buf[tag]
+        B.gto_expand_tree_fused(self.cfg, H, W_draft, b["dstats"], b["pool"], self.workspace)
+        B.gto_select_topg(self.cfg, b["pool"], b["tree"])
+        B.gto_tree_reward_fused(self.cfg, b["tree"], H, W_target, b["tstats"], b["reward"], self.workspace)
+
+    def step(self, H_cur, H_ref, W_draft, W_target):
+        self.build_and_score("cur", H_cur, W_draft, W_target)
+        self.build_and_score("ref", H_ref, W_draft, W_target)
+        cur, ref = self.buf["cur"], self.buf["ref"]
+        B.gto_group_advantage(self.cfg, cur["reward"]["reward"], ref["reward"]["reward"], self.adv)
+        B.gto_ppo_surrogate_fwd_fused(self.cfg, cur["tree"], cur["reward"], H_cur, H_ref, W_draft, cur["dstats"],
+                                      ref["dstats"], self.adv, self.ppo, self.workspace)
+        if self.want_grad:
+            B.gto_ppo_surrogate_bwd_fused(self.cfg, cur["tree"], cur["reward"], self.ppo, H_cur, W_draft, cur["dstats"],
+                                          self.grad_rows, self.grad_slot, self.workspace)

@@ -1,0 +1,135 @@
+"""GPU parity of the fused LM-head variant (logits = hidden . W^T on the matrix cores, never stored)
+against the CPU oracle fed the fp64 logits of the same hidden states and heads.
+
+The GPU accumulates the logits in fp32, so every logit carries an absolute error of up to E (checked
+here against the oracle's fp64 value; see logit_error_bound).  Consequences, all derived from E:
+row top-k / argmax are compared where the oracle's row margins are clear of E; tree decisions where
+the oracle's audit (with E in its error budget) says so; floats within max(1e-5, 4 d E) relative.
+The staged protocol is otherwise that of test_gpu_parity.py."""
+import numpy as np
+import pytest
+import torch
+
+import gto_synth as S
+import gpu_util as U
+import paper_2509_22134_amd as G
+from oracle import gto_oracle as O
+from paper_2509_22134_amd.pipeline import GtoFusedPath
+from test_gpu_parity import _compare_ppo, _say
+
+pytestmark = pytest.mark.gpu
+
+
+def logit_error_bound(hidden, max_abs_logit):
+    """Absolute error granted to an fp32-accumulated logit: 2^-21 per unit of the largest |logit|
+    (a few fp32 roundings of the running sum), growing like the square root of the number of
+    accumulation steps beyond 1024."""
+    return 2.0 ** -21 * max_abs_logit * max(1.0, (hidden / 1024.0) ** 0.5)
+
+
+def _oracle_logits(t, roots):
+    H = {n: t[n][roots].float().cpu().numpy() for n in ("H_cur", "H_ref")}
+    W = {n: t[n].float().cpu().numpy() for n in ("W_draft", "W_target")}
+    return {"D_cur": O.fused_logits(H["H_cur"], W["W_draft"]), "T_cur": O.fused_logits(H["H_cur"], W["W_target"]),
+            "D_ref": O.fused_logits(H["H_ref"], W["W_draft"]), "T_ref": O.fused_logits(H["H_ref"], W["W_target"])}
+
+
+def _run(w, t, device, flags=0):
+    path = GtoFusedPath(R=t["H_cur"].shape[0], d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m,
+                        device=device, eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags)
+    if flags == 0:
+        path.grad_rows.fill_(7.0)
+    path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"])
+    torch.cuda.synchronize()
+    return path
+
+
+def _compare_fused(w, t, path, roots):
+    L = _oracle_logits(t, roots)
+    E = logit_error_bound(w.hidden, max(float(np.abs(v).max()) for v in L.values()))
+    rtol = max(1e-5, 4 * w.d * E)
+    ora = O.full_path(L["D_cur"], L["T_cur"], L["D_ref"], L["T_ref"], k=w.k, d=w.d, g=w.g, m=1, eta=w.eta,
+                      eps=w.eps, delta=w.delta, want_grad=False, logit_err=E)
+    n_ambig = 0
+    m = U.used_mask(len(roots), w.d, w.k)
+    for tag in ("cur", "ref"):
+        b = path.buf[tag]
+        gd = {k: v[roots] for k, v in U.to_np(b["dstats"]).items()}
+        gt = {k: v[roots] for k, v in U.to_np(b["tstats"]).items()}
+        gpool = {k: v[roots] for k, v in U.to_np(b["pool"]).items()}
+        gtree = {k: v[roots] for k, v in U.to_np(b["tree"]).items()}
+        grew = {k: v[roots] for k, v in U.to_np(b["reward"]).items()}
+        o, Dn, Tn = ora[tag], L["D_" + tag], L["T_" + tag]
+        # stage 1: the GPU's logits at its own top tokens are the oracle's within E; statistics within E
+        g_logit = gd["top_logp"].astype(np.float64) + gd["row_lse"].astype(np.float64)[..., None]
+        o_at = np.take_along_axis(Dn, gd["top_tok"].astype(np.int64).clip(0, w.V - 1), axis=-1)
+        assert np.abs(g_logit - o_at)[m].max() <= E + 4e-6, float(np.abs(g_logit - o_at)[m].max())
+        assert np.abs(gd["row_lse"] - o["dstats"]["row_lse"])[m].max() <= E + 2e-6
+        assert np.abs(gt["t_lse"] - o["tstats"]["t_lse"])[m].max() <= E + 2e-6
+        assert np.abs(gd["row_max"] - o["dstats"]["row_max"])[m].max() <= E
+        rm_d, rm_t = O.row_margins(Dn, w.k, E), O.row_margins(Tn, 1, E)
+        clear_rows = (rm_d >= 1.0) & (rm_t >= 1.0)
+        for r in np.nonzero(clear_rows)[0]:
+            assert np.array_equal(gd["top_tok"][r][m[r]], o["dstats"]["top_tok"][r][m[r]]), (tag, r)
+            assert np.array_equal(gt["t_argmax"][r][m[r]], o["tstats"]["t_argmax"][r][m[r]]), (tag, r)
+        # stage 2: oracle logic on the GPU's own statistics, bit for bit
+        pool2, tree2, rew2, path2 = U.oracle_from_gpu_stats(gd, gt, Tn, w.d, w.k, w.g, w.eta)
+        U.check_stage2(gpool, gtree, grew, pool2, tree2, rew2, path2, rtol=rtol)
+        # stage 3: end to end where every decision is clear of the logit error
+        margin = np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"])
+        clear = np.nonzero((margin >= 1.0) & clear_rows)[0]
+        n_ambig += len(roots) - len(clear)
+        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear,
+                       exact_scores=False, rtol=rtol)
+    return L, n_ambig
+
+
+@pytest.mark.parametrize("R,d,k,g,hidden,V,corr", [
+    (16, 3, 4, 12, 256, 3000, 0.9),        # ragged vocabulary tail, one row block with a tail
+    (40, 3, 8, 20, 512, 5120, 0.9),        # two row blocks, list capacity 8
+    (16, 4, 10, 30, 128, 2048, 0.8),       # k = 10: list capacity 16
+    (16, 3, 4, 12, 256, 1024, 0.0),        # independent target head: mostly empty paths
+])
+def test_fused_full_path_matches_oracle(gpu_device, R, d, k, g, hidden, V, corr):
+    w = S.FusedWorkload("case", R=R, V=V, k=k, d=d, g=g, m=8, hidden=hidden, h_scale=3.0, w_sigma=0.05,
+                        w_corr=corr, ref_sigma=0.05)
+    _say(f"fused full path R={R} d={d} k={k} g={g} hidden={hidden} V={V} corr={corr}")
+    t = S.make_fused(w, gpu_device)
+    path = _run(w, t, gpu_device)
+    L, n_ambig = _compare_fused(w, t, path, list(range(R)))
+    _say(f"  near-tie roots: {n_ambig}")
+    _compare_ppo(w, L, path)
+    assert n_ambig <= R            # of 2 R trees
+
+
+def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
+    _say("fused: chunk count / workgroup layout invariance")
+    w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    t = S.make_fused(w, gpu_device)
+    try:
+        ref = _run(w, t, gpu_device)
+        for nc, patches in ((1, False), (3, True), (16, True)):
+            G.gto_set_fused_tuning(nc, patches)
+            other = _run(w, t, gpu_device)
+            for tag in ("cur", "ref"):
+                for grp in ("tree", "reward"):
+                    for n, x in ref.buf[tag][grp].items():
+                        if x.dtype == torch.int32:
+                            assert torch.equal(x, other.buf[tag][grp][n]), (nc, tag, grp, n)
+            assert torch.equal(ref.grad_slot, other.grad_slot)
+            v = ref.grad_slot >= 0
+            torch.testing.assert_close(ref.grad_rows[v], other.grad_rows[v], rtol=1e-5, atol=1e-9)
+    finally:
+        G.gto_set_fused_tuning(0, True)
+
+
+def test_fused_zero_fill(gpu_device):
+    w = S.FusedWorkload("case", R=16, V=2048, k=4, d=3, g=12, m=8, hidden=128, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    t = S.make_fused(w, gpu_device)
+    a = _run(w, t, gpu_device)
+    b = _run(w, t, gpu_device, flags=G.GTO_FLAG_GRAD_ZERO_FILL)
+    v = a.grad_slot >= 0
+    assert torch.equal(a.grad_slot, b.grad_slot) and torch.equal(a.grad_rows[v], b.grad_rows[v])
+    assert not b.grad_rows[~v].any() and bool((a.grad_rows[~v] == 7.0).all())

@@ -61,3 +61,21 @@ def test_target_stats_argmax_lowest_id_and_lse():
             assert st["t_argmax"][r, l, j] == min(v for v in range(40) if row[v] == row.max())
             np.testing.assert_allclose(st["t_lse"][r, l, j], sp.logsumexp(row), rtol=1e-14)
             assert st["t_max"][r, l, j] == row.max()
+
+
+def test_fused_logits_is_the_plain_dot_product_and_row_margins_flag_close_tops():
+    rng = np.random.default_rng(3)
+    R, d, k, Hd, V = 2, 2, 2, 5, 7
+    H = rng.integers(-8, 8, size=(R, d, k, Hd)).astype(np.float32) / 4     # bf16-exact values
+    W = rng.integers(-8, 8, size=(V, Hd)).astype(np.float32) / 8
+    L = O.fused_logits(H, W)
+    for r in range(R):
+        for (l, j) in O.used_slots(d, k):
+            for v in range(V):
+                want = sum(float(H[r, l, j, h]) * float(W[v, h]) for h in range(Hd))
+                assert L[r, l, j, v] == want                               # exact: small dyadic rationals
+    assert not L[:, 0, 1:].any()
+    X = np.zeros((1, 1, 2, 6))
+    X[0, 0, 0] = [5.0, 4.0, 3.0, 2.9999, 0.0, -1.0]
+    assert O.row_margins(X, 2, 1e-3)[0] == pytest.approx(1.0 / 2e-3)       # top-3 gaps: 1, 1
+    assert O.row_margins(X, 3, 1e-3)[0] < 1.0                              # 3 vs 2.9999 is inside the error

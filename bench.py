@@ -25,6 +25,67 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix peak
+
+
+def bench_fused(args, torch, S, G):
+    """The fifth workload: hidden states x LM head on the matrix cores, logits never stored."""
+    from paper_2509_22134_amd.pipeline import GtoFusedPath
+    dev = torch.device("cuda:0")
+    w = S.FUSED_CONFIGS[args.workload]
+    if args.roots:
+        w = S.scaled(w, R=args.roots)
+    t = S.make_fused(w, dev)
+    path = GtoFusedPath(R=w.R, d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m, device=dev,
+                        eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5)
+
+    def step():
+        path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    G.gto_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    G.gto_profile_enable(False)
+    prof = G.gto_profile_read()
+    kernels = {n: {"launches": c, "avg_ms": ms / c} for n, (c, ms) in prof.items()}
+    dom = "fused_rows_draft"
+    flops = 2.0 * w.R * w.rho * w.V * w.hidden
+    dom_ms = kernels[dom]["avg_ms"]
+    achieved = flops / (dom_ms * 1e-3) / 1e12
+    out = {
+        "metric": "draft trees scored/sec (build+reward+PPO), fused LM head, V=%d" % w.V,
+        "value": 2 * w.R / (dt / args.steps), "unit": "trees/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: R={w.R} hidden={w.hidden} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m}, "
+                               "bf16 hidden states x bf16 LM heads, full path, current + reference tree per root"},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "flops_per_launch": flops, "avg_launch_ms": dom_ms},
+        "kernels": kernels,
+    }
+    if args.cpu_roots > 0:
+        import numpy as np
+        from oracle import gto_oracle as O
+        n = min(2, w.R)
+        t0 = time.perf_counter()
+        H = {k: t[k][:n].float().cpu().numpy() for k in ("H_cur", "H_ref")}
+        Wd, Wt = t["W_draft"].float().cpu().numpy(), t["W_target"].float().cpu().numpy()
+        L = {"D_cur": O.fused_logits(H["H_cur"], Wd), "T_cur": O.fused_logits(H["H_cur"], Wt),
+             "D_ref": O.fused_logits(H["H_ref"], Wd), "T_ref": O.fused_logits(H["H_ref"], Wt)}
+        O.full_path(L["D_cur"], L["T_cur"], L["D_ref"], L["T_ref"], k=w.k, d=w.d, g=w.g, m=1, eta=w.eta, eps=w.eps,
+                    delta=w.delta, grad_scale=0.5)
+        dtc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2 * n / dtc, "unit": "trees/s", "cores": os.cpu_count(), "kind": "oracle",
+                               "sample": f"first {n} roots (2 trees each, fp64 matmuls through the BLAS numpy links, "
+                                         f"then the full path incl. gradient), {dtc:.1f} s"}
+    print(json.dumps(out))
 
 
 def cpu_baseline(w, tens, n_roots, torch):
@@ -70,6 +131,9 @@ def main():
     if not os.path.exists(G.lib_path()):
         from paper_2509_22134_amd.build import build_lib
         build_lib()
+    if args.workload in S.FUSED_CONFIGS:
+        bench_fused(args, torch, S, G)
+        return
     dev = torch.device("cuda:0")
     w = S.CONFIGS[args.workload]
     if args.roots:

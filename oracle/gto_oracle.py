@@ -73,11 +73,14 @@ def fused_logits(H: np.ndarray, W_vh: np.ndarray) -> np.ndarray:
     padding slots are left at zero; they are never read."""
     R, d, k, Hd = H.shape
     V = W_vh.shape[0]
-    Wt = np.ascontiguousarray(W_vh.astype(np.float64).T)
+    W64 = W_vh.astype(np.float64, copy=False)
+    slots = used_slots(d, k)
     out = np.zeros((R, d, k, V))
     for r in range(R):
-        for (l, j) in used_slots(d, k):
-            out[r, l, j] = H[r, l, j].astype(np.float64) @ Wt
+        rows = np.stack([H[r, l, j] for (l, j) in slots]).astype(np.float64)      # [rho, Hd]
+        prod = rows @ W64.T                                                       # one matmul per root
+        for i, (l, j) in enumerate(slots):
+            out[r, l, j] = prod[i]
     return out
 
 

@@ -199,7 +199,8 @@ FusedPlan fused_plan(int64_t M, int V, int ktop) {
   p.M = M;
   p.m_blocks = (int)((M + 255) / 256);
   p.n_tiles = (V + 255) / 256;
-  int nc = g_fused_chunks > 0 ? g_fused_chunks : (2048 + p.m_blocks - 1) / p.m_blocks;
+  // aim at ~14 workgroups per compute unit; a multiple of 8 chunks fills the per-XCD patches
+  int nc = g_fused_chunks > 0 ? g_fused_chunks : (((3584 + p.m_blocks - 1) / p.m_blocks + 7) / 8) * 8;
   if (nc > 64) nc = 64;
   if (nc > p.n_tiles) nc = p.n_tiles;
   if (nc < 1) nc = 1;

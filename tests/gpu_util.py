@@ -62,24 +62,25 @@ def oracle_from_gpu_stats(gd, gt, T_np, d, k, g, eta):
     return pool, tree, rew, path
 
 
-def _scores_equal(a, b, exact):
+def _scores_equal(a, b, exact, atol=4e-6):
     if exact:
         return np.array_equal(a, b)
     fin = np.isfinite(b)
     return np.array_equal(np.isfinite(a), fin) and \
-        np.all(np.abs(a[fin].astype(np.float64) - b[fin]) <= 1e-6 * np.abs(b[fin]) + 4e-6)
+        np.all(np.abs(a[fin].astype(np.float64) - b[fin]) <= 1e-6 * np.abs(b[fin]) + atol)
 
 
-def check_stage2(gpool, gtree, grew, opool, otree, orew, opath, roots=None, exact_scores=True, rtol=1e-5):
+def check_stage2(gpool, gtree, grew, opool, otree, orew, opath, roots=None, exact_scores=True, rtol=1e-5,
+                 score_atol=4e-6):
     """Every integer output bit-exact.  Scores: bit-exact when both sides started from the same fp32
     row statistics (stage 2); within a few fp32 roundings against the pure fp64 oracle (stage 3)."""
     sl = slice(None) if roots is None else roots
     for name in INT_POOL:
         assert np.array_equal(gpool[name][sl], opool[name][sl]), name
-    assert _scores_equal(gpool["cand_score"][sl], opool["cand_score"][sl], exact_scores), "cand_score"
+    assert _scores_equal(gpool["cand_score"][sl], opool["cand_score"][sl], exact_scores, score_atol), "cand_score"
     for name in INT_TREE:
         assert np.array_equal(gtree[name][sl], otree[name][sl]), name
-    assert _scores_equal(gtree["sel_score"][sl], otree["sel_score"][sl], exact_scores), "sel_score"
+    assert _scores_equal(gtree["sel_score"][sl], otree["sel_score"][sl], exact_scores, score_atol), "sel_score"
     for name in INT_PATH:
         assert np.array_equal(grew[name][sl], opath[name][sl]), name
     assert np.array_equal(grew["n_leaves"][sl], orew["n_leaves"][sl])

@@ -37,7 +37,8 @@ def bench_fused(args, torch, S, G):
         w = S.scaled(w, R=args.roots)
     t = S.make_fused(w, dev)
     path = GtoFusedPath(R=w.R, d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m, device=dev,
-                        eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5)
+                        eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5,
+                        flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE)
 
     def step():
         path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"])
@@ -64,7 +65,10 @@ def bench_fused(args, torch, S, G):
         "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 x bf16 -> f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: R={w.R} hidden={w.hidden} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m}, "
-                               "bf16 hidden states x bf16 LM heads, full path, current + reference tree per root"},
+                               "bf16 hidden states x bf16 LM heads, full path, current + reference tree per root",
+                   "target_rows": "all used slots" if args.no_prune else "only slots with a kept child",
+                   "target_rows_multiplied": [int(path.buf[x]["tree"]["slot_need"].sum().item()) for x in ("cur", "ref")],
+                   "draft_rows": w.R * w.rho},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "flops_per_launch": flops, "avg_launch_ms": dom_ms},

@@ -219,7 +219,7 @@ FusedPlan fused_plan(int64_t M, int V, int ktop) {
 
 // Workspace of the fused calls: [partials of the row pass | gathered single logits].
 struct FusedWs {
-  size_t partial_bytes, off_slot, off_tok, off_out0, off_out1, bytes;
+  size_t partial_bytes, off_slot, off_tok, off_out0, off_out1, off_list, off_count, bytes;
 };
 FusedWs fused_ws(const gto_config *c) {
   FusedWs w{};
@@ -233,7 +233,9 @@ FusedWs fused_ws(const gto_config *c) {
   w.off_tok = up(w.off_slot + n * sizeof(int64_t));
   w.off_out0 = up(w.off_tok + n * sizeof(int32_t));
   w.off_out1 = up(w.off_out0 + n * sizeof(float));
-  w.bytes = up(w.off_out1 + n * sizeof(float));
+  w.off_list = up(w.off_out1 + n * sizeof(float));            // compacted slot list of a pruned target pass
+  w.off_count = up(w.off_list + (size_t)c->R * c->d * c->k * sizeof(int32_t));
+  w.bytes = w.off_count + 256;
   // the backward pass lays the same memory out differently
   const size_t rd = (size_t)c->R * c->d;
   const size_t bwd = fused_plan((int64_t)rd, c->V, 1).bytes + 2 * up(rd * sizeof(int32_t)) + 256;
@@ -266,7 +268,8 @@ void run_gather(const gto_config *c, const gto_tree *t, const gto_reward *path, 
 }
 
 int run_fused_rows(const gto_config *c, const void *hidden, int hidden_dim, const void *w, int ktop,
-                   const int32_t *row_list, int64_t n_list, int out_by_list, float *row_max, float *row_lse,
+                   const int32_t *row_list, int64_t n_list, const int32_t *n_dev, int out_by_list, float *row_max,
+                   float *row_lse,
                    int32_t *top_tok, float *top_logp, float *top_logit, void *ws, size_t ws_bytes,
                    const char *name, hipStream_t st) {
   const int64_t M = row_list ? n_list : (int64_t)c->R * rows_per_root(c);
@@ -275,7 +278,7 @@ int run_fused_rows(const gto_config *c, const void *hidden, int hidden_dim, cons
   char *base = static_cast<char *>(ws);
   gto::FusedArgs a{};
   a.hidden = hidden; a.w = w; a.hidden_dim = hidden_dim; a.V = c->V; a.rho = rows_per_root(c); a.d = c->d;
-  a.kslots = c->k; a.ktop = ktop; a.M = M; a.row_list = row_list; a.out_by_list = out_by_list;
+  a.kslots = c->k; a.ktop = ktop; a.M = M; a.m_dev = n_dev; a.row_list = row_list; a.out_by_list = out_by_list;
   a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
   a.xcd_patches = g_fused_patches;
   a.part_s = reinterpret_cast<double *>(base + p.off_s);
@@ -509,7 +512,7 @@ int gto_fused_draft_row_stats(const gto_config *cfg, const void *hidden, int32_t
                               size_t workspace_bytes, void *hip_stream) {
   GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_vh));
   GTO_TRY(check_draft_stats(stats_out));
-  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, cfg->k, nullptr, 0, 0, stats_out->row_max,
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, cfg->k, nullptr, 0, nullptr, 0, stats_out->row_max,
                          stats_out->row_lse, stats_out->top_tok, stats_out->top_logp, top_logit_or_null,
                          workspace, workspace_bytes, "fused_rows_draft", (hipStream_t)hip_stream));
   return hip_status();
@@ -520,7 +523,7 @@ int gto_fused_target_row_stats(const gto_config *cfg, const void *hidden, int32_
                                void *hip_stream) {
   GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_vh));
   GTO_TRY(check_target_stats(stats_out));
-  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, 1, nullptr, 0, 0, stats_out->t_max, stats_out->t_lse,
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_vh, 1, nullptr, 0, nullptr, 0, stats_out->t_max, stats_out->t_lse,
                          stats_out->t_argmax, nullptr, nullptr, workspace, workspace_bytes, "fused_rows_target",
                          (hipStream_t)hip_stream));
   return hip_status();
@@ -534,7 +537,7 @@ int gto_expand_tree_fused(const gto_config *cfg, const void *hidden, int32_t hid
   GTO_TRY(check_pool(pool_out));
   GTO_TRY(check_ws(workspace, workspace_bytes, fused_ws(cfg).bytes));
   hipStream_t st = (hipStream_t)hip_stream;
-  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_draft_vh, cfg->k, nullptr, 0, 0, stats_out->row_max,
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_draft_vh, cfg->k, nullptr, 0, nullptr, 0, stats_out->row_max,
                          stats_out->row_lse, stats_out->top_tok, stats_out->top_logp, nullptr, workspace,
                          workspace_bytes, "fused_rows_draft", st));
   run_expand(cfg, stats_out, pool_out, st);
@@ -552,7 +555,17 @@ int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const voi
   const FusedWs L = fused_ws(cfg);
   GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
   hipStream_t st = (hipStream_t)hip_stream;
-  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_target_vh, 1, nullptr, 0, 0, stats_out->t_max,
+  const int32_t *list = nullptr, *count = nullptr;
+  int64_t cap = 0;
+  if (cfg->flags & GTO_FLAG_TARGET_PRUNE) {
+    // only the slots whose node has a kept child are multiplied: compact them into a row list
+    int32_t *l = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + L.off_list);
+    int32_t *c = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + L.off_count);
+    ProfScope ps("compact_needed_slots", st);
+    gto::launch_compact_flags(tree->slot_need, cfg->R * cfg->d * cfg->k, l, c, st);
+    list = l; count = c; cap = (int64_t)cfg->R * rows_per_root(cfg);
+  }
+  GTO_TRY(run_fused_rows(cfg, hidden, hidden_dim, w_target_vh, 1, list, cap, count, 0, stats_out->t_max,
                          stats_out->t_lse, stats_out->t_argmax, nullptr, nullptr, workspace, workspace_bytes,
                          "fused_rows_target", st));
   float *node_logit = reinterpret_cast<float *>(static_cast<char *>(workspace) + L.off_out0);

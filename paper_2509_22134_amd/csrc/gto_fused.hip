@@ -342,6 +342,7 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 // One wave per row: merge the chunk partials into the final statistics.
 __global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
   const int64_t g = blockIdx.x;
+  if (a.m_dev && g >= (int64_t)*a.m_dev) return;
   const int lane = threadIdx.x;
   const int nc = a.n_chunks, ktop = a.ktop;
   const int64_t oi = a.row_list ? (a.out_by_list ? g : (int64_t)a.row_list[g])
@@ -438,6 +439,38 @@ __global__ __launch_bounds__(1024) void k_bwd_rows(BwdRowsArgs a) {
     __syncthreads();
   }
   if (tid == 0) *a.count = s_base;
+}
+
+// Ordered compaction (single workgroup) of the slots whose flag is set: list of slot indices + count.
+__global__ __launch_bounds__(1024) void k_compact_flags(const int32_t *flags, int n, int32_t *list, int32_t *count) {
+  __shared__ int s_wave[16];
+  __shared__ int s_base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_base = 0;
+  __syncthreads();
+  for (int p0 = 0; p0 < n; p0 += 1024) {
+    const int p = p0 + tid;
+    const bool valid = (p < n) && (flags[p] != 0);
+    const uint64_t bal = __builtin_amdgcn_ballot_w64(valid);
+    const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wave[wave] = __builtin_popcountll(bal);
+    __syncthreads();
+    int off = s_base;
+    for (int w = 0; w < wave; ++w) off += s_wave[w];
+    if (valid) list[off + before] = p;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int w = 0; w < 16; ++w) tot += s_wave[w];
+      s_base += tot;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) *count = s_base;
+}
+
+void launch_compact_flags(const int32_t *flags, int n, int32_t *list, int32_t *count, hipStream_t st) {
+  hipLaunchKernelGGL(k_compact_flags, dim3(1), dim3(1024), 0, st, flags, n, list, count);
 }
 
 __global__ void k_zero_rows(float *grad_rows, const int32_t *grad_slot, int V) {

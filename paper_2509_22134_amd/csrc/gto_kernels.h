@@ -132,6 +132,7 @@ void launch_fused_rows(const FusedArgs &a, hipStream_t st);
 void launch_fused_bwd_fixup(const FusedArgs &a, hipStream_t st);
 void launch_bwd_rows(const BwdRowsArgs &a, hipStream_t st);
 void launch_zero_rows(float *grad_rows, const int32_t *grad_slot, int rows, int V, hipStream_t st);
+void launch_compact_flags(const int32_t *flags, int n, int32_t *list, int32_t *count, hipStream_t st);
 void launch_fused_merge(const FusedArgs &a, hipStream_t st);
 void launch_gather_dot(const GatherDotArgs &a, hipStream_t st);
 void set_waves_per_row(int w);

@@ -130,6 +130,30 @@ def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
         G.gto_set_fused_tuning(0, True)
 
 
+def test_fused_target_pruning_changes_nothing_but_the_rows_multiplied(gpu_device):
+    _say("fused: target-row pruning")
+    w = S.FusedWorkload("case", R=40, V=3000, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    t = S.make_fused(w, gpu_device)
+    a = _run(w, t, gpu_device)
+    b = _run(w, t, gpu_device, flags=G.GTO_FLAG_TARGET_PRUNE)
+    for tag in ("cur", "ref"):
+        need = a.buf[tag]["tree"]["slot_need"].bool()
+        frac = need.float().sum().item() / (w.R * w.rho)
+        _say(f"  {tag}: {frac:.2f} of the target rows are needed")
+        assert 0.05 < frac < 0.95
+        for n, x in a.buf[tag]["tstats"].items():
+            assert torch.equal(x[need], b.buf[tag]["tstats"][n][need]), n
+            assert not b.buf[tag]["tstats"][n][~need].any(), n
+        for grp in ("tree", "reward"):
+            for n, x in a.buf[tag][grp].items():
+                assert torch.equal(x, b.buf[tag][grp][n]), (tag, grp, n)
+    for n, x in a.ppo.items():
+        assert torch.equal(x, b.ppo[n]), n
+    v = a.grad_slot >= 0
+    assert torch.equal(a.grad_slot, b.grad_slot) and torch.equal(a.grad_rows[v], b.grad_rows[v])
+
+
 def test_fused_zero_fill(gpu_device):
     w = S.FusedWorkload("case", R=16, V=2048, k=4, d=3, g=12, m=8, hidden=128, h_scale=3.0, w_sigma=0.05,
                         w_corr=0.9, ref_sigma=0.05)

@@ -211,6 +211,23 @@ int gto_ppo_surrogate_bwd(const gto_config *cfg, const gto_tree *tree_cur,
                           const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
                           float *grad_rows, int32_t *grad_slot, void *hip_stream);
 
+/* Token-level loss of Eq. 13 / App. B.2: mean over the supervised positions of the cross-entropy
+ * H(p_T, p_M) = -sum_v p_T(v) log p_M(v) from the target's to the draft's next-token distribution under
+ * the same teacher-forced prefix, i.e. at the root slot (0, 0) of every root.  The row statistics must
+ * hold the lse of slot (0, 0) of both tensors (gto_expand_tree / gto_tree_reward leave them there, also
+ * with target pruning).  `weight_or_null` [R] selects the supervised positions (1 / 0; NULL = all).
+ * Forward: loss_rows [R], loss [1] and inv_count [1] = 1 / |I|.  Backward: grad_rows0 [R, V] fp32 =
+ * grad_scale * weight / |I| * (softmax(draft) - softmax(target)), the gradient of grad_scale * loss
+ * w.r.t. the draft logits of slot (0, 0). */
+int gto_token_loss_fwd(const gto_config *cfg, const void *draft_logits, const void *target_logits,
+                       const gto_draft_stats *draft_stats, const gto_target_stats *target_stats,
+                       const float *weight_or_null, float *loss_rows, float *loss, float *inv_count,
+                       void *hip_stream);
+int gto_token_loss_bwd(const gto_config *cfg, const void *draft_logits, const void *target_logits,
+                       const gto_draft_stats *draft_stats, const gto_target_stats *target_stats,
+                       const float *weight_or_null, const float *inv_count, float grad_scale, float *grad_rows0,
+                       void *hip_stream);
+
 /* ---- Fused LM-head variant (the fifth workload: logits never reach HBM) -------------------------
  * The logits of slot (l, j) of root r are hidden[r, l, j, :] . w_vh[v, :] for v < V, accumulated in
  * fp32 on the matrix cores and consumed as fp32 (never rounded to bf16).  `hidden` is bf16

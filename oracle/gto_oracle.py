@@ -26,6 +26,7 @@ Optimization for Speculative Decoding"):
   * Sec. 3.2 "Tree Reward Optimization": Eq. 6-7 grouping, Eq. 9 debiased reward,
     Eq. 10 group standardisation, Eq. 11 geometric-mean likelihood ratio on the
     longest accepted sequence, Eq. 12 clipped surrogate; Algorithm 1.
+  * Eq. 13 and App. B.2: token-level cross-entropy from the target to the draft distribution.
   * App. B.1/B.3: k = 10, g = 60, depth 7, eta = 1, m = 8.
 
 Readings where the paper is silent (each is repeated next to the code it affects):
@@ -538,6 +539,34 @@ def ppo_surrogate_bwd(path, tree, fwd, D_cur, d_lse, adv, m: int, grad_scale: fl
             gvec[tok] += c
             grad_rows[r, t] = gvec
     return dict(grad_rows=grad_rows, grad_slot=grad_slot, coef=coef)
+
+
+# --------------------------------------------------------------------- token-level loss
+def token_loss(D: np.ndarray, T: np.ndarray, weight=None, grad_scale: float = 1.0):
+    """Token-level loss of Eq. 13 / App. B.2: mean over the supervised positions of the cross-entropy
+    H(p_T, p_M) = - sum_v p_T(v) log p_M(v) from the target's to the draft's next-token distribution
+    under the same teacher-forced prefix, i.e. at the root slot (0, 0) of every root.  `weight`
+    (0/1 per root) selects the supervised positions I(x); default all.  Returns loss_rows [R]
+    (H per root, 0 where unsupervised), loss (mean over I), and grad [R, V] = d(grad_scale * loss) /
+    d(draft logits of slot (0,0)) = grad_scale * w_r / |I| * (p_M - p_T)."""
+    R, V = D.shape[0], D.shape[-1]
+    w = np.ones(R) if weight is None else np.asarray(weight, dtype=np.float64)
+    n = float(w.sum())
+    loss_rows = np.zeros(R)
+    grad = np.zeros((R, V))
+    for r in range(R):
+        x = D[r, 0, 0].astype(np.float64)
+        t = T[r, 0, 0].astype(np.float64)
+        _, lse_m = _row_lse(x)
+        _, lse_t = _row_lse(t)
+        p_t = np.exp(t - lse_t)
+        p_m = np.exp(x - lse_m)
+        fin = p_t > 0                       # 0 * log 0 := 0 (zero-probability target tokens add nothing)
+        loss_rows[r] = w[r] * float(-(p_t[fin] * (x[fin] - lse_m)).sum())
+        if n > 0:
+            grad[r] = grad_scale * w[r] / n * (p_m - p_t)
+    loss = float(loss_rows.sum() / n) if n > 0 else 0.0
+    return dict(loss_rows=loss_rows, loss=loss, grad=grad)
 
 
 # ------------------------------------------------------------------------ whole path

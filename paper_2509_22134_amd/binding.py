@@ -89,6 +89,8 @@ def lib():
     L.gto_ppo_surrogate_bwd.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, P(gto_draft_stats),
                                         VP, VP, VP]
     L.gto_calibration_copy.argtypes = [VP, VP, SZ, VP]
+    L.gto_token_loss_fwd.argtypes = [cfgp, VP, VP, P(gto_draft_stats), P(gto_target_stats), VP, VP, VP, VP, VP]
+    L.gto_token_loss_bwd.argtypes = [cfgp, VP, VP, P(gto_draft_stats), P(gto_target_stats), VP, VP, C.c_float, VP, VP]
     L.gto_fused_workspace_bytes.argtypes = [cfgp, C.c_int32, P(SZ)]
     L.gto_fused_draft_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), VP, VP, SZ, VP]
     L.gto_fused_target_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_target_stats), VP, SZ, VP]
@@ -106,7 +108,7 @@ def lib():
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
-                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy",
+                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
                  "gto_set_fused_tuning", "gto_expand_tree_fused", "gto_tree_reward_fused",
                  "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused"):
@@ -358,6 +360,24 @@ def gto_ppo_surrogate_bwd_fused(cfg, tree_cur, path_cur, fwd, hidden_cur, w_draf
 
 def gto_set_fused_tuning(n_chunks: int = 0, xcd_patches: bool = True) -> None:
     _check(lib().gto_set_fused_tuning(int(n_chunks), 1 if xcd_patches else 0), "gto_set_fused_tuning")
+
+
+def gto_token_loss_fwd(cfg, draft_logits, target_logits, draft_stats, target_stats, weight, loss_rows, loss,
+                       inv_count, stream=None):
+    ds, ts = _pack(gto_draft_stats, _DRAFT, draft_stats), _pack(gto_target_stats, _TARGET, target_stats)
+    _check(lib().gto_token_loss_fwd(C.byref(cfg), _dp(draft_logits), _dp(target_logits), _ref(ds), _ref(ts),
+                                    _dp(weight), _dp(loss_rows), _dp(loss), _dp(inv_count), _stream(stream)),
+           "gto_token_loss_fwd")
+    return loss_rows, loss
+
+
+def gto_token_loss_bwd(cfg, draft_logits, target_logits, draft_stats, target_stats, weight, inv_count, grad_scale,
+                       grad_rows0, stream=None):
+    ds, ts = _pack(gto_draft_stats, _DRAFT, draft_stats), _pack(gto_target_stats, _TARGET, target_stats)
+    _check(lib().gto_token_loss_bwd(C.byref(cfg), _dp(draft_logits), _dp(target_logits), _ref(ds), _ref(ts),
+                                    _dp(weight), _dp(inv_count), float(grad_scale), _dp(grad_rows0), _stream(stream)),
+           "gto_token_loss_bwd")
+    return grad_rows0
 
 
 def gto_calibration_copy(src, dst, stream=None):

@@ -671,6 +671,49 @@ int gto_set_fused_tuning(int n_chunks, int xcd_patches) {
   return GTO_OK;
 }
 
+int gto_token_loss_fwd(const gto_config *cfg, const void *draft_logits, const void *target_logits,
+                       const gto_draft_stats *draft_stats, const gto_target_stats *target_stats,
+                       const float *weight_or_null, float *loss_rows, float *loss, float *inv_count,
+                       void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, false));
+  GTO_TRY(check_logits(draft_logits));
+  GTO_TRY(check_logits(target_logits));
+  if (!draft_stats || !draft_stats->row_lse || !target_stats || !target_stats->t_lse || !loss_rows || !loss ||
+      !inv_count)
+    return GTO_E_NULL;
+  gto::TokenLossArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.V = cfg->V; a.row_stride = cfg->row_stride;
+  a.draft_logits = draft_logits; a.target_logits = target_logits;
+  a.d_lse = draft_stats->row_lse; a.t_lse = target_stats->t_lse; a.weight = weight_or_null;
+  a.loss_rows = loss_rows; a.loss = loss; a.inv_count_out = inv_count;
+  {
+    ProfScope ps("token_loss_fwd", (hipStream_t)hip_stream);
+    gto::launch_token_loss(a, cfg->dtype, false, (hipStream_t)hip_stream);
+  }
+  return hip_status();
+}
+
+int gto_token_loss_bwd(const gto_config *cfg, const void *draft_logits, const void *target_logits,
+                       const gto_draft_stats *draft_stats, const gto_target_stats *target_stats,
+                       const float *weight_or_null, const float *inv_count, float grad_scale, float *grad_rows0,
+                       void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, false));
+  GTO_TRY(check_logits(draft_logits));
+  GTO_TRY(check_logits(target_logits));
+  if (!draft_stats || !draft_stats->row_lse || !target_stats || !target_stats->t_lse || !inv_count || !grad_rows0)
+    return GTO_E_NULL;
+  gto::TokenLossArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.V = cfg->V; a.row_stride = cfg->row_stride;
+  a.draft_logits = draft_logits; a.target_logits = target_logits;
+  a.d_lse = draft_stats->row_lse; a.t_lse = target_stats->t_lse; a.weight = weight_or_null;
+  a.grad_scale = grad_scale; a.inv_count = inv_count; a.grad = grad_rows0;
+  {
+    ProfScope ps("token_loss_bwd", (hipStream_t)hip_stream);
+    gto::launch_token_loss(a, cfg->dtype, true, (hipStream_t)hip_stream);
+  }
+  return hip_status();
+}
+
 int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
   if (!src || !dst) return GTO_E_NULL;
   if (bytes == 0 || bytes % 16 != 0) return GTO_E_SHAPE;

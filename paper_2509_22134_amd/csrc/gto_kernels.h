@@ -135,6 +135,18 @@ void launch_zero_rows(float *grad_rows, const int32_t *grad_slot, int rows, int 
 void launch_compact_flags(const int32_t *flags, int n, int32_t *list, int32_t *count, hipStream_t st);
 void launch_fused_merge(const FusedArgs &a, hipStream_t st);
 void launch_gather_dot(const GatherDotArgs &a, hipStream_t st);
+struct TokenLossArgs {
+  int R, d, k, V;
+  int64_t row_stride;
+  const void *draft_logits, *target_logits;
+  const float *d_lse, *t_lse;      // [R, d, k] statistics (entry of slot (0,0) is used)
+  const float *weight;             // optional [R]
+  float grad_scale;
+  float *loss_rows, *loss, *inv_count_out;   // forward outputs: [R], [1], [1] = 1 / |I|
+  const float *inv_count;          // backward input: the forward's 1 / |I|
+  float *grad;                     // backward output [R, V]
+};
+void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t st);
 void set_waves_per_row(int w);
 int get_waves_per_row();
 void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st);

@@ -364,6 +364,88 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
   if (own_tok) out[tok] = (float)((double)coef * s_part[0]);
 }
 
+// ------------------------------------------------------------------------------- token-level loss
+// One workgroup per root: streams the root rows (slot (0,0)) of the draft and the target logits
+// together.  Forward: H = lse_M - sum_v p_T(v) d_v.  Backward: scale * (p_M - p_T) as an fp32 row.
+template <typename T, bool BWD>
+__global__ __launch_bounds__(256) void k_token_loss(TokenLossArgs a) {
+  const int r = blockIdx.x;
+  const float w = a.weight ? a.weight[r] : 1.f;
+  const int64_t si = stat_index(r, 0, 0, a.d, a.k);
+  const T *__restrict__ drow = static_cast<const T *>(a.draft_logits) + si * a.row_stride;
+  const T *__restrict__ trow = static_cast<const T *>(a.target_logits) + si * a.row_stride;
+  const float d_lse = a.d_lse[si], t_lse = a.t_lse[si];
+  const int V = a.V;
+  if (BWD) {
+    float *__restrict__ out = a.grad + (int64_t)r * V;
+    const float scale = a.grad_scale * w * a.inv_count[0];
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+      const float pm = __builtin_amdgcn_exp2f((Elem<T>::load1(drow + i) - d_lse) * kLog2e);
+      const float pt = __builtin_amdgcn_exp2f((Elem<T>::load1(trow + i) - t_lse) * kLog2e);
+      out[i] = scale * (pm - pt);
+    }
+    return;
+  }
+  double acc = 0.0;
+  for (int i0 = threadIdx.x * 8; i0 < V; i0 += blockDim.x * 8) {
+    float part = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (i0 + e < V) {
+        const float tv = Elem<T>::load1(trow + i0 + e);
+        const float pt = __builtin_amdgcn_exp2f((tv - t_lse) * kLog2e);
+        const float dv = Elem<T>::load1(drow + i0 + e);
+        part += (pt > 0.f) ? pt * (dv - d_lse) : 0.f;      // 0 * log 0 := 0
+      }
+    }
+    acc += (double)part;
+  }
+  __shared__ double s_red[256];
+  s_red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a.loss_rows[r] = (float)(-(double)w * s_red[0]);
+}
+
+// single workgroup: |I| = sum of weights, loss = sum of rows / |I| (fixed-shape tree reductions)
+__global__ __launch_bounds__(256) void k_token_loss_mean(TokenLossArgs a) {
+  __shared__ double s_a[256], s_b[256];
+  double sa = 0.0, sb = 0.0;
+  for (int r = threadIdx.x; r < a.R; r += 256) {
+    sa += (double)a.loss_rows[r];
+    sb += a.weight ? (double)a.weight[r] : 1.0;
+  }
+  s_a[threadIdx.x] = sa;
+  s_b[threadIdx.x] = sb;
+  __syncthreads();
+  for (int off = 128; off >= 1; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      s_a[threadIdx.x] += s_a[threadIdx.x + off];
+      s_b[threadIdx.x] += s_b[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double n = s_b[0];
+    a.loss[0] = (n > 0.0) ? (float)(s_a[0] / n) : 0.f;
+    a.inv_count_out[0] = (n > 0.0) ? (float)(1.0 / n) : 0.f;
+  }
+}
+
+void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t st) {
+  if (bwd) {
+    if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, true>), dim3(a.R), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_token_loss<float, true>), dim3(a.R), dim3(256), 0, st, a);
+    return;
+  }
+  if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, false>), dim3(a.R), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((k_token_loss<float, false>), dim3(a.R), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_token_loss_mean, dim3(1), dim3(256), 0, st, a);
+}
+
 // ------------------------------------------------------------------------------- calibration copy
 // Plain 16-byte-per-lane copy of a known size: the yardstick that hardware HBM counters of the
 // row kernels are scaled by.

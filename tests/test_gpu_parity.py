@@ -376,3 +376,37 @@ def test_full_size_config_sampled_roots(gpu_device, name, sample):
         np.testing.assert_allclose(gp["loss"][0], gp["loss_group"].astype(np.float64).mean(), rtol=1e-5, atol=1e-7)
     del tens, path
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------ token-level loss
+@pytest.mark.parametrize("name,R,V,kw", [("llama31_8b", 16, 20000, {}), ("tiny", 8, 1000, {}),
+                                         ("llama31_8b", 8, 5003, {"pad": 5008})])
+def test_token_level_loss_fwd_bwd(gpu_device, name, R, V, kw):
+    pad = kw.get("pad")
+    w = S.scaled(S.CONFIGS[name], R=R, V=pad or V)
+    _say(f"token-level loss {name} R={R} V={V}")
+    tens = S.make_logits(w, gpu_device, want=("D_cur", "T_cur"))
+    D, T = tens["D_cur"], tens["T_cur"]
+    T[0, 0, 0, 7:V:3] = float("-inf")                       # zero-probability target tokens
+    if pad:
+        D[..., V:] = 50.0
+        T[..., V:] = 50.0
+    cfg = G.make_config(R=R, d=w.d, k=w.k, g=w.g, V=V, dtype=w.torch_dtype, row_stride=pad)
+    ds = G.gto_draft_row_stats(cfg, D, G.alloc_draft_stats(cfg, gpu_device))
+    ts = G.gto_target_row_stats(cfg, T, G.alloc_target_stats(cfg, gpu_device))
+    weight = torch.ones(R, device=gpu_device)
+    weight[1] = 0.0
+    loss_rows = torch.empty(R, device=gpu_device); loss = torch.empty(1, device=gpu_device)
+    inv = torch.empty(1, device=gpu_device); grad = torch.empty((R, V), device=gpu_device)
+    Dn, Tn = U.logits_np(D)[..., :V], U.logits_np(T)[..., :V]
+    for wt, wn in ((None, None), (weight, weight.cpu().numpy())):
+        G.gto_token_loss_fwd(cfg, D, T, ds, ts, wt, loss_rows, loss, inv)
+        G.gto_token_loss_bwd(cfg, D, T, ds, ts, wt, inv, 0.7, grad)
+        torch.cuda.synchronize()
+        ref = O.token_loss(Dn, Tn, wn, 0.7)
+        np.testing.assert_allclose(loss_rows.cpu().numpy(), ref["loss_rows"], rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(loss.item(), ref["loss"], rtol=1e-5)
+        g = grad.cpu().numpy()
+        for r in range(R):
+            scale = np.abs(ref["grad"][r]).max()
+            assert np.abs(g[r] - ref["grad"][r]).max() <= 1e-5 * scale + 1e-12, r

@@ -157,3 +157,39 @@ def test_full_path_composition_runs_and_is_consistent():
     np.testing.assert_allclose(out["adv"], O.group_advantage(out["cur"]["reward"]["reward_lse"],
                                                             out["ref"]["reward"]["reward_lse"], m))
     assert out["bwd"]["grad_rows"].shape == (R, d, V)
+
+
+def test_token_loss_matches_scipy_entropy_kl_and_finite_differences():
+    import scipy.special as sp
+    rng = np.random.default_rng(8)
+    R, d, k, V = 5, 2, 2, 9
+    D = rng.normal(0, 1.5, (R, d, k, V)); T = rng.normal(0, 1.5, (R, d, k, V))
+    out = O.token_loss(D, T)
+    for r in range(R):
+        pt, pm = sp.softmax(T[r, 0, 0]), sp.softmax(D[r, 0, 0])
+        # H(p_T, p_M) = H(p_T) + KL(p_T || p_M)   (App. B.2)
+        want = scipy.stats.entropy(pt) + scipy.stats.entropy(pt, pm)
+        assert abs(out["loss_rows"][r] - want) < 1e-12
+    assert abs(out["loss"] - out["loss_rows"].mean()) < 1e-15
+    # same distribution: cross-entropy = entropy; one-hot target: plain negative log-likelihood
+    same = O.token_loss(D, D)
+    np.testing.assert_allclose(same["loss_rows"], [scipy.stats.entropy(sp.softmax(D[r, 0, 0])) for r in range(R)], rtol=1e-12)
+    assert np.abs(same["grad"]).max() < 1e-16
+    Th = np.full_like(T, -np.inf); tok = rng.integers(0, V, R)
+    for r in range(R):
+        Th[r, 0, 0, tok[r]] = 0.0
+    hot = O.token_loss(D, Th)
+    np.testing.assert_allclose(hot["loss_rows"], [-sp.log_softmax(D[r, 0, 0])[tok[r]] for r in range(R)], rtol=1e-12)
+    # gradient: central finite differences, with a mask and a scale; only slot (0,0) matters
+    w = np.array([1, 0, 1, 1, 0.0]); gs = 0.7
+    ref = O.token_loss(D, T, w, gs)
+    assert ref["loss_rows"][1] == 0 and not ref["grad"][1].any()
+    h = 1e-6
+    for r in range(R):
+        for v in range(V):
+            Dp, Dm = D.copy(), D.copy(); Dp[r, 0, 0, v] += h; Dm[r, 0, 0, v] -= h
+            fd = gs * (O.token_loss(Dp, T, w)["loss"] - O.token_loss(Dm, T, w)["loss"]) / (2 * h)
+            assert abs(fd - ref["grad"][r, v]) < 1e-8
+    Dq = D.copy(); Dq[:, 1] += 3.0
+    assert O.token_loss(Dq, T)["loss"] == out["loss"]
+    assert np.abs(ref["grad"].sum(axis=-1)).max() < 1e-15

@@ -46,12 +46,15 @@ typedef enum gto_status {
   GTO_E_SHAPE = -2,     /* a size is outside the limits above                           */
   GTO_E_ALIGN = -3,     /* logits base or row stride not 16-byte aligned                */
   GTO_E_DTYPE = -4,     /* cfg->dtype is not GTO_BF16 / GTO_F32                         */
-  GTO_E_MODE = -5,      /* cfg->reward_mode unknown, or eta/eps/delta not usable        */
+  GTO_E_MODE = -5,      /* cfg->reward_mode / path_mode unknown, or eta/eps/delta not usable */
   GTO_E_WORKSPACE = -6, /* workspace missing, misaligned or smaller than required       */
   GTO_E_HIP = -7        /* a launch failed; gto_strerror(GTO_E_HIP) has the HIP message */
 } gto_status;
 
 enum { GTO_BF16 = 0, GTO_F32 = 1 };
+/* Longest accepted sequence (Sec. 3.2): GREEDY = the sequence greedy (T = 0) target verification
+ * accepts (default); MAX_L = the root-to-leaf sequence with the largest expected acceptance length. */
+enum { GTO_PATH_GREEDY = 0, GTO_PATH_MAX_L = 1 };
 enum { GTO_REWARD_LSE = 0, GTO_REWARD_MAX = 1, GTO_REWARD_MEAN = 2, GTO_REWARD_NODESUM = 3 };
 enum {
   GTO_FLAG_GRAD_ZERO_FILL = 1, /* bwd also writes zeros into rows that carry no gradient                */
@@ -71,7 +74,7 @@ typedef struct gto_config {
   float delta;          /* std floor of Eq. 10                                             */
   float grad_scale;     /* upstream dL/dL_GTO (the paper's omega = 0.5 in Eq. 13)          */
   int32_t flags;        /* GTO_FLAG_*                                                      */
-  int32_t reserved;     /* must be 0                                                       */
+  int32_t path_mode;    /* GTO_PATH_*: which sequence the surrogate is taken along           */
 } gto_config;
 
 /* Row statistics of a draft-logits tensor.  Entries of padding slots are not written. */

@@ -447,6 +447,33 @@ def accepted_path(tree, t_argmax: np.ndarray, d: int):
     return dict(path_len=path_len, path_node=path_node, path_slot=path_slot)
 
 
+def max_l_path(tree, node_cum: np.ndarray, d: int):
+    """Alternative reading of the "longest accepted sequence" (Sec. 3.2): the root-to-leaf sequence
+    of the kept tree whose expected acceptance length L_i (Eq. 3) is largest, the first such leaf
+    in kept order among equals.  Same outputs as accepted_path; the length is the leaf's depth."""
+    R, g = tree["sel_tok"].shape
+    path_len = np.zeros(R, dtype=np.int32)
+    path_node = np.full((R, d), -1, dtype=np.int32)
+    path_slot = np.full((R, d), -1, dtype=np.int32)
+    for r in range(R):
+        n = int(tree["n_sel"][r])
+        best, bl = -1, -1.0
+        for i in range(n):
+            if tree["sel_leaf"][r, i] and node_cum[r, i] > bl:
+                best, bl = i, node_cum[r, i]
+        chain = []
+        p = best
+        while p >= 0:
+            chain.append(p)
+            p = int(tree["sel_parent"][r, p])
+        chain.reverse()
+        path_len[r] = len(chain)
+        for t, node in enumerate(chain):
+            path_node[r, t] = node
+            path_slot[r, t] = tree["sel_pslot"][r, node]
+    return dict(path_len=path_len, path_node=path_node, path_slot=path_slot)
+
+
 # ---------------------------------------------------------------------- advantage
 def group_advantage(r_cur, r_ref, m: int, delta: float = 1e-6):
     """Eq. 9-10: debias against the reference tree, then standardise inside each
@@ -571,7 +598,7 @@ def token_loss(D: np.ndarray, T: np.ndarray, weight=None, grad_scale: float = 1.
 
 # ------------------------------------------------------------------------ whole path
 def full_path(D_cur, T_cur, D_ref, T_ref, *, k, d, g, m, eta=1.0, eps=0.2, delta=1e-6,
-              grad_scale=1.0, reward_mode="lse", want_grad=True, logit_err=0.0):
+              grad_scale=1.0, reward_mode="lse", want_grad=True, logit_err=0.0, path_mode="greedy"):
     """Algorithm 1, lines for one minibatch of R roots, composed from the steps
     above.  D_ref doubles as the reference model's logits at the current tree's
     slot coordinates (Eq. 11 denominator)."""
@@ -582,7 +609,7 @@ def full_path(D_cur, T_cur, D_ref, T_ref, *, k, d, g, m, eta=1.0, eps=0.2, delta
         tree = select_topg(pool, g, audit=True)
         ts = target_row_stats(T)
         rew = tree_reward(tree, T, ts["t_lse"], eta)
-        path = accepted_path(tree, ts["t_argmax"], d)
+        path = accepted_path(tree, ts["t_argmax"], d) if path_mode == "greedy" else max_l_path(tree, rew["node_cum"], d)
         out[tag] = dict(dstats=ds, pool=pool, tree=tree, tstats=ts, reward=rew, path=path)
     key = "reward_" + reward_mode
     adv = group_advantage(out["cur"]["reward"][key], out["ref"]["reward"][key], m, delta)

@@ -9,6 +9,7 @@ import torch
 
 GTO_BF16, GTO_F32 = 0, 1
 GTO_REWARD_LSE, GTO_REWARD_MAX, GTO_REWARD_MEAN, GTO_REWARD_NODESUM = 0, 1, 2, 3
+GTO_PATH_GREEDY, GTO_PATH_MAX_L = 0, 1
 GTO_FLAG_GRAD_ZERO_FILL = 1
 GTO_FLAG_TARGET_PRUNE = 2
 
@@ -27,7 +28,7 @@ class gto_config(C.Structure):
     _fields_ = [("R", C.c_int32), ("d", C.c_int32), ("k", C.c_int32), ("g", C.c_int32), ("V", C.c_int32),
                 ("dtype", C.c_int32), ("row_stride", C.c_int64), ("group_size", C.c_int32),
                 ("reward_mode", C.c_int32), ("eta", C.c_float), ("eps", C.c_float), ("delta", C.c_float),
-                ("grad_scale", C.c_float), ("flags", C.c_int32), ("reserved", C.c_int32)]
+                ("grad_scale", C.c_float), ("flags", C.c_int32), ("path_mode", C.c_int32)]
 
     @property
     def C(self):
@@ -118,11 +119,11 @@ def lib():
 
 
 def make_config(*, R, d, k, g, V, dtype, row_stride=None, group_size=1, reward_mode=GTO_REWARD_LSE,
-                eta=1.0, eps=0.2, delta=1e-6, grad_scale=1.0, flags=0) -> gto_config:
+                eta=1.0, eps=0.2, delta=1e-6, grad_scale=1.0, flags=0, path_mode=0) -> gto_config:
     if isinstance(dtype, torch.dtype):
         dtype = GTO_BF16 if dtype == torch.bfloat16 else GTO_F32
     return gto_config(R, d, k, g, V, dtype, V if row_stride is None else row_stride, group_size, reward_mode,
-                      eta, eps, delta, grad_scale, flags, 0)
+                      eta, eps, delta, grad_scale, flags, path_mode)
 
 
 # ------------------------------------------------------------------ output containers (torch = memory only)

@@ -64,7 +64,7 @@ int check_cfg(const gto_config *c, bool need_group) {
   if ((c->row_stride * elem_size(c->dtype)) % 16 != 0) return GTO_E_ALIGN;
   if (c->reward_mode < GTO_REWARD_LSE || c->reward_mode > GTO_REWARD_NODESUM) return GTO_E_MODE;
   if (!(c->eta > 0.f) || !(c->eps >= 0.f) || !(c->delta >= 0.f)) return GTO_E_MODE;
-  if (c->reserved != 0) return GTO_E_MODE;
+  if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L) return GTO_E_MODE;
   if (need_group && (c->group_size < 1 || c->R % c->group_size != 0)) return GTO_E_SHAPE;
   return GTO_OK;
 }
@@ -162,6 +162,7 @@ void run_reward(const gto_config *c, const gto_tree *t, const void *logits, cons
                 const gto_reward *w, hipStream_t st) {
   gto::RewardArgs a{};
   a.R = c->R; a.d = c->d; a.k = c->k; a.g = c->g; a.dtype = c->dtype; a.reward_mode = c->reward_mode;
+  a.path_mode = c->path_mode;
   a.row_stride = c->row_stride; a.eta = c->eta;
   a.target_logits = logits; a.t_lse = s->t_lse; a.t_argmax = s->t_argmax;
   a.sel_tok = t->sel_tok; a.sel_parent = t->sel_parent; a.sel_depth = t->sel_depth;
@@ -573,6 +574,7 @@ int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const voi
   {
     gto::RewardArgs a{};
     a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.dtype = cfg->dtype; a.reward_mode = cfg->reward_mode;
+    a.path_mode = cfg->path_mode;
     a.row_stride = 0; a.eta = cfg->eta;
     a.target_logits = nullptr; a.node_logit = node_logit; a.t_lse = stats_out->t_lse; a.t_argmax = stats_out->t_argmax;
     a.sel_tok = tree->sel_tok; a.sel_parent = tree->sel_parent; a.sel_depth = tree->sel_depth;

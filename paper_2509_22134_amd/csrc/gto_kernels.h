@@ -47,7 +47,7 @@ struct SelectArgs {
 };
 
 struct RewardArgs {
-  int R, d, k, g, dtype, reward_mode;
+  int R, d, k, g, dtype, reward_mode, path_mode;
   int64_t row_stride;
   float eta;
   const void *target_logits;

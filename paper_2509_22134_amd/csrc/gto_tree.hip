@@ -244,6 +244,30 @@ __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
     a.n_leaves[r] = (int)cnt;
   }
 
+  if (a.path_mode == 1) {
+    // alternative reading of "longest accepted sequence": the root-to-leaf sequence with the largest
+    // expected acceptance length L_i (first one in kept order among equals)
+    __syncthreads();
+    for (int q = 0, i = tid; i < n; i += kRewardThreads, ++q) s_logt[i] = myL[q];   // -1 for non-leaves
+    __syncthreads();
+    if (tid == 0) {
+      int best = -1;
+      double bl = -1.0;
+      for (int i = 0; i < n; ++i)
+        if (s_logt[i] > bl) { bl = s_logt[i]; best = i; }
+      int chain[kMaxDepth];
+      int len = 0;
+      for (int p = best; p >= 0 && len < kMaxDepth; p = s_parent[p]) chain[len++] = p;
+      for (int t = 0; t < d; ++t) {
+        const bool on = t < len;
+        const int node = on ? chain[len - 1 - t] : -1;
+        a.path_node[(int64_t)r * d + t] = node;
+        a.path_slot[(int64_t)r * d + t] = on ? a.sel_pslot[sel0 + node] : -1;
+      }
+      a.path_len[r] = len;
+    }
+    return;
+  }
   // greedy verification walk (T = 0): follow the kept child that equals the target argmax
   int cur = -1, slot = 0, len = 0;
   bool alive = true;

@@ -27,11 +27,12 @@ def _say(msg):
 
 
 def _run_full(w, tens, device, row_stride=None, V=None, ref_stats_known=True, flags=0, reward_mode=0,
-              grad_scale=0.5):
+              grad_scale=0.5, path_mode=0):
     V = V or w.V
     path = GtoPath(R=tens["D_cur"].shape[0], d=w.d, k=w.k, g=w.g, V=V, dtype=w.torch_dtype, group_size=w.m,
                    device=device, row_stride=row_stride, eta=w.eta, eps=w.eps, delta=w.delta,
-                   grad_scale=grad_scale, flags=flags, reward_mode=reward_mode, full_path=w.full_path)
+                   grad_scale=grad_scale, flags=flags, reward_mode=reward_mode, full_path=w.full_path,
+                   path_mode=path_mode)
     if flags == 0 and w.full_path:
         path.grad_rows.fill_(7.0)       # untouched rows must stay untouched
     path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"), ref_stats_known=ref_stats_known)
@@ -192,6 +193,9 @@ def test_tiny_config_full_path(gpu_device):
     ("tiny", 8, 400, {"g": 500}),                              # g >= C: everything kept
     ("tiny", 8, 64, {"d": 1, "k": 8, "g": 4}),                 # single level
     ("vicuna13b", 16, 8000, {"full_path": True}),
+    ("llama31_8b", 8, 8000, {"d": 7, "g": 50}),                # tree-configuration sweep of App. E:
+    ("llama31_8b", 8, 8000, {"d": 8, "g": 70}),                # depth {6, 7, 8} x budget {50, 60, 70}
+    ("llama31_8b", 8, 8000, {"d": 7, "g": 60}),                # the paper's own setting (App. B.1)
 ])
 def test_mid_size_full_path(gpu_device, name, R, V, kw):
     kw = dict(kw)
@@ -267,6 +271,23 @@ def test_target_row_pruning_changes_nothing_but_the_rows_read(gpu_device):
         assert torch.equal(t, b.ppo[n]), n
     assert torch.equal(a.grad_slot, b.grad_slot) and torch.equal(a.grad_rows, b.grad_rows)
     _compare_all(w, tens, a)                              # slot_need itself is checked against the oracle here
+
+
+def test_max_l_reading_of_the_longest_accepted_sequence(gpu_device):
+    _say("path mode: branch with the largest expected acceptance length")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=12000)
+    tens = S.make_logits(w, gpu_device)
+    path = _run_full(w, tens, gpu_device, path_mode=G.GTO_PATH_MAX_L)
+    Tn = {"cur": U.logits_np(tens["T_cur"]), "ref": U.logits_np(tens["T_ref"])}
+    for tag in ("cur", "ref"):
+        b = path.buf[tag]
+        gd, gt, grew = U.to_np(b["dstats"]), U.to_np(b["tstats"]), U.to_np(b["reward"])
+        pool2, tree2, rew2, _ = U.oracle_from_gpu_stats(gd, gt, Tn[tag], w.d, w.k, w.g, w.eta)
+        path2 = O.max_l_path(tree2, rew2["node_cum"], w.d)
+        for n in U.INT_PATH:
+            assert np.array_equal(grew[n], path2[n]), (tag, n)
+        assert (grew["path_len"] >= 1).all()              # a tree always has a best branch
+    _compare_ppo(w, tens, path)
 
 
 def test_bitwise_deterministic(gpu_device):

@@ -155,3 +155,22 @@ def test_walk_stops_at_unexpanded_child_and_on_random_targets():
         kept, expanded = brute.build_tree(D[r], 3, 4, 20)
         walk = brute.greedy_accept([p for p, _ in kept], expanded, T[r], 4)
         assert path["path_len"][r] == len(walk)
+
+
+def test_max_l_path_is_the_branch_with_the_largest_expected_length():
+    D, T, pool, tree, ts = _case(41, 6, 4, 3, 10, 14)
+    rew = O.tree_reward(tree, T, ts["t_lse"], 1.0)
+    path = O.max_l_path(tree, rew["node_cum"], 4)
+    for r in range(6):
+        kept, expanded = brute.build_tree(D[r], 3, 4, 14)
+        Ls = brute.sequence_lengths([p for p, _ in kept], expanded, T[r])
+        best = max(Ls.values())
+        winners = [p for p, L in Ls.items() if L == best]
+        assert len(winners) == 1
+        opaths = brute.oracle_paths(pool, tree, r)
+        l = int(path["path_len"][r])
+        assert l == len(winners[0])
+        assert [opaths[i] for i in path["path_node"][r, :l]] == [winners[0][:j + 1] for j in range(l)]
+        for t in range(l):
+            assert expanded[winners[0][:t]] == (t, int(path["path_slot"][r, t]))
+        assert (path["path_node"][r, l:] == -1).all() and (path["path_slot"][r, l:] == -1).all()

@@ -3,8 +3,10 @@
 // never reach HBM.
 //
 //  k_fused_rows  : 256 x 256 output tile per workgroup iteration (4 waves, each 128 x 128 as 4 x 4
-//                  MFMA 32x32x16 bf16 tiles, fp32 accumulators), K-slabs of 64 double-buffered in
-//                  LDS.  A workgroup owns 256 rows and sweeps a chunk of the vocabulary; after each
+//                  MFMA 32x32x16 bf16 tiles, fp32 accumulators).  K slabs of 32 go from global
+//                  memory straight into a ring of four LDS stages (no register staging), three
+//                  slabs in flight while one is multiplied.
+//                  A workgroup owns 256 rows and sweeps a chunk of the vocabulary; after each
 //                  tile the accumulators are staged through LDS so that thread t owns row t and
 //                  folds its 256 new logits into its running (max, sum, top-k list) in registers.
 //  k_fused_merge : combines the per-chunk partials of a row into the final statistics.
@@ -13,24 +15,31 @@
 #include "gto_device.h"
 #include "gto_kernels.h"
 
-#ifndef GTO_FUSED_PITCH_PAD
-#define GTO_FUSED_PITCH_PAD 0   // experiments only: extra elements between rows of hidden and W
-#endif
-#ifndef GTO_FUSED_EXP
-#define GTO_FUSED_EXP 0   // experiments only: 1 = no global loads in the main loop, 2 = one MFMA per k step
-#endif
-
 namespace gto {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int FBM = 256, FBN = 256, FBK = 64;
-constexpr int FLD = FBK + 8;                       // padded LDS row (elements): 144 bytes
-constexpr int FSTAGE = (FBM + FBN) * FLD;          // elements per stage
+constexpr int FBM = 256, FBN = 256;
+constexpr int FBK = 32;                            // k extent of one LDS stage
+constexpr int FROWB = FBK * 2;                     // bytes per staged row (bf16)
+constexpr int FSTAGE_B = (FBM + FBN) * FROWB;      // bytes per stage: 256 hidden rows, then 256 W rows
+constexpr int FNST = 4;                            // LDS stages: one being multiplied, FNST-1 landing
 constexpr int FKT = 16;                            // capacity of the per-thread top list
 constexpr int FSTG_LD = 65;                        // staging row stride (floats)
-constexpr size_t kFusedLdsBytes = (size_t)2 * FSTAGE * sizeof(uint16_t);
+constexpr size_t kFusedLdsBytes = (size_t)FNST * FSTAGE_B;
+static_assert(kFusedLdsBytes >= (size_t)FBM * FSTG_LD * sizeof(float), "staging area must fit");
+static_assert(FNST == 4, "the wait counts in the main loop are written for three slabs in flight");
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
+// lds_addr + 16 l (lds_addr is wave-uniform and travels in M0); counted by vmcnt.
+__device__ __forceinline__ void load_to_lds16(unsigned lds_addr, const void *g) {
+  unsigned keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "s"(lds_addr), "v"(g)
+               : "memory");
+}
 
 // index of the statistics entry (= logits slot) of the q-th used row of root r
 __device__ __forceinline__ int64_t used_slot_index(int64_t gidx, int rho, int d, int k) {
@@ -104,17 +113,22 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   const uint16_t *__restrict__ Hp = static_cast<const uint16_t *>(a.hidden);
   const uint16_t *__restrict__ Wp = static_cast<const uint16_t *>(a.w);
 
-  // global -> LDS copy assignment: 8 chunks of 16 bytes per operand per thread
-  const int ld_row = tid >> 3, ld_kc = tid & 7;          // rows ld_row + 32 i, i = 0..7
-  int64_t a_off[8];
+  // global -> LDS assignment: one wave instruction fills 16 rows x 64 bytes; wave w issues the
+  // row groups 64 w + 16 j (j = 0..3) of both operands.  Lane l lands at row l/4, 16-byte unit
+  // l%4 of its group; it fetches the unit (l%4) ^ ((row/4)%4) of that row, so that the fragment
+  // reads below (32 rows at one k unit) spread over all LDS banks.
+  const int ld_row = 64 * wave + (lane >> 2);            // + 16 j
+  const int ld_unit = (lane & 3) ^ ((lane >> 4) & 3);
+  const uint16_t *a_ptr[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int64_t g = row0 + ld_row + 32 * i;
+  for (int j = 0; j < 4; ++j) {
+    int64_t g = row0 + ld_row + 16 * j;
     if (g >= M) g = M - 1;
     const int64_t slot = a.row_list ? (int64_t)a.row_list[g] : used_slot_index(g, a.rho, a.d, a.kslots);
-    a_off[i] = slot * (HD + GTO_FUSED_PITCH_PAD) + ld_kc * 8;
+    a_ptr[j] = Hp + slot * HD + ld_unit * 8;
   }
-
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)lds;
+  const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)wave * 4096u);
   // the list keeps the KT >= ktop best of the row; its last entry is the insertion threshold
   RowState<KT> st;
   st.m = neg_inf(); st.c = 0.f; st.s = 0.0;
@@ -141,12 +155,12 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 
   for (int tile = tile0; tile < tile1; ++tile) {
     const int n0 = tile * FBN;
-    int64_t b_off[8];
+    const uint16_t *b_ptr[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int n = n0 + ld_row + 32 * i;
+    for (int j = 0; j < 4; ++j) {
+      int n = n0 + ld_row + 16 * j;
       if (n >= a.V) n = a.V - 1;
-      b_off[i] = (int64_t)n * (HD + GTO_FUSED_PITCH_PAD) + ld_kc * 8;
+      b_ptr[j] = Wp + (int64_t)n * HD + ld_unit * 8;
     }
     f32x16 acc[4][4];
 #pragma unroll
@@ -156,89 +170,78 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    u32x4 ra[8], rb[8];
-    // prologue: slab 0 -> stage 0
+    // k slab s lands in stage s % FNST; every wave issues 4 + 4 loads per slab (pair j = one
+    // 16-row group of each operand)
+    auto issue_pair = [&](int s_, int j) {
+      const unsigned sb = wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024;
+      load_to_lds16(sb, a_ptr[j] + s_ * FBK);
+      load_to_lds16(sb + FBM * FROWB, b_ptr[j] + s_ * FBK);
+    };
+    __syncthreads();                           // previous tile's epilogue no longer reads the staging area
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      ra[i] = *reinterpret_cast<const u32x4 *>(Hp + a_off[i]);
-      rb[i] = *reinterpret_cast<const u32x4 *>(Wp + b_off[i]);
-    }
-    __syncthreads();   // previous tile's epilogue no longer reads the staging area
+    for (int s_ = 0; s_ < FNST - 1; ++s_)
+      if (s_ < kt_count)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4 *>(lds + (ld_row + 32 * i) * FLD + ld_kc * 8) = ra[i];
-      *reinterpret_cast<u32x4 *>(lds + (FBM + ld_row + 32 * i) * FLD + ld_kc * 8) = rb[i];
-    }
+        for (int j = 0; j < 4; ++j) issue_pair(s_, j);
+    if (kt_count < FNST - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");        // slab 0 landed, two slabs in flight
     __syncthreads();
 
-    // Fragment addresses of this lane inside a stage (elements): row (lane & 31) of each 32-row
-    // tile, 8 consecutive k starting at 8 * (lane >> 5) within each 16-wide k step.
-    const int fa_base = (wm * 128 + (lane & 31)) * FLD + (lane >> 5) * 8;
-    const int fb_base = (FBM + wn * 128 + (lane & 31)) * FLD + (lane >> 5) * 8;
+    // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
+    // 16-byte unit 2 h + (lane >> 5) of k half h sits at unit ^ ((row / 4) % 4).
+    const int fsw = ((lane >> 5) ^ ((lane >> 2) & 3)) * 16;
+    const int fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
+    const int fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
+    const unsigned char *ldsb = reinterpret_cast<const unsigned char *>(lds);
     bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      fa[0][t] = *reinterpret_cast<const bf16x8 *>(lds + fa_base + t * 32 * FLD);
-      fb[0][t] = *reinterpret_cast<const bf16x8 *>(lds + fb_base + t * 32 * FLD);
+      fa[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fa_base + t * 32 * FROWB);
+      fb[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fb_base + t * 32 * FROWB);
     }
+    // One k slab: 16 MFMAs per half.  While the first half runs, the fragments of the second half
+    // are read; between the halves the wave makes sure slab kt+1 has landed; while the second half
+    // runs, the loads of slab kt+3 are issued and the first fragments of slab kt+1 are read.  The
+    // LDS and memory instructions sit between the MFMA rows so that the matrix pipe never waits
+    // for their issue.
     for (int kt = 0; kt < kt_count; ++kt) {
-      const int cur = kt & 1;
-      const uint16_t *sS = lds + cur * FSTAGE;
-      const bool more = (kt + 1 < kt_count);
-#if GTO_FUSED_EXP != 1
-      if (more) {
-        const int k1 = (kt + 1) * FBK;
+      const unsigned char *sS = ldsb + (kt % FNST) * FSTAGE_B;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          ra[i] = *reinterpret_cast<const u32x4 *>(Hp + a_off[i] + k1);
-          rb[i] = *reinterpret_cast<const u32x4 *>(Wp + b_off[i] + k1);
-        }
-      }
-#endif
-      // software pipeline over the four 16-wide k steps of the slab: the fragments of step kk+1
-      // are read from LDS while the 16 MFMAs of step kk run
+      for (int i = 0; i < 4; ++i) {
+        fa[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fa_base ^ 32) + i * 32 * FROWB);
+        fb[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fb_base ^ 32) + i * 32 * FROWB);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kk = 0; kk < FBK / 16; ++kk) {
-        const int cb = kk & 1, nb = cb ^ 1;
-        if (kk + 1 < FBK / 16) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            fa[nb][t] = *reinterpret_cast<const bf16x8 *>(sS + fa_base + t * 32 * FLD + (kk + 1) * 16);
-            fb[nb][t] = *reinterpret_cast<const bf16x8 *>(sS + fb_base + t * 32 * FLD + (kk + 1) * 16);
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the MFMAs they overlap with
-#if GTO_FUSED_EXP == 2
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][0] + fa[cb][1] + fa[cb][2] + fa[cb][3],
-                                                            fb[cb][0] + fb[cb][1] + fb[cb][2] + fb[cb][3],
-                                                            acc[0][0], 0, 0, 0);
-#else
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
-#endif
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (more) {
-        uint16_t *dS = lds + (cur ^ 1) * FSTAGE;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          *reinterpret_cast<u32x4 *>(dS + (ld_row + 32 * i) * FLD + ld_kc * 8) = ra[i];
-          *reinterpret_cast<u32x4 *>(dS + (FBM + ld_row + 32 * i) * FLD + ld_kc * 8) = rb[i];
-        }
+      const bool has_next = kt + 1 < kt_count;
+      const bool has_load = kt + FNST - 1 < kt_count;
+      if (has_next) {
+        // this wave's share of slab kt+1 has landed when at most the loads of slab kt+2 are still
+        // out; the barrier extends that to the other waves' shares, and tells that every wave is
+        // past its reads of slab kt-1, whose stage the next loads overwrite
+        if (kt + 2 < kt_count) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
       }
-      __syncthreads();
-      if (more) {
-        const uint16_t *nS = lds + (cur ^ 1) * FSTAGE;
+      const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          fa[0][t] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + t * 32 * FLD);
-          fb[0][t] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + t * 32 * FLD);
+      for (int i = 0; i < 4; ++i) {
+        if (has_load) issue_pair(kt + FNST - 1, i);
+        if (has_next) {
+          fa[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + i * 32 * FROWB);
+          fb[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + i * 32 * FROWB);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    __syncthreads();                           // all fragment reads done before the staging area is written
 
     // ---- epilogue: four 64-column quarters through the staging area; thread t owns row t
     float *stg = reinterpret_cast<float *>(lds);
@@ -248,13 +251,15 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-          for (int n2 = 0; n2 < 2; ++n2)
+          for (int n2 = 0; n2 < 2; ++n2) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
               const int row = wm * 128 + mt * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
               const int col = n2 * 32 + (lane & 31);
               stg[row * FSTG_LD + col] = acc[mt][(qd & 1) * 2 + n2][e];
             }
+            __builtin_amdgcn_sched_barrier(0);   // 16 accumulator reads at a time keep the register pressure low
+          }
       }
       __syncthreads();
       {

@@ -24,12 +24,22 @@ constexpr int FBM = 256, FBN = 256;
 constexpr int FBK = 32;                            // k extent of one LDS stage
 constexpr int FROWB = FBK * 2;                     // bytes per staged row (bf16)
 constexpr int FSTAGE_B = (FBM + FBN) * FROWB;      // bytes per stage: 256 hidden rows, then 256 W rows
-constexpr int FNST = 4;                            // LDS stages: one being multiplied, FNST-1 landing
+constexpr int FNST = 4;                            // LDS stages: one being multiplied, FNST-1 landing (3 and 5 measured slower)
 constexpr int FKT = 16;                            // capacity of the per-thread top list
 constexpr int FSTG_LD = 65;                        // staging row stride (floats)
 constexpr size_t kFusedLdsBytes = (size_t)FNST * FSTAGE_B;
 static_assert(kFusedLdsBytes >= (size_t)FBM * FSTG_LD * sizeof(float), "staging area must fit");
-static_assert(FNST == 4, "the wait counts in the main loop are written for three slabs in flight");
+static_assert(FNST >= 3 && FNST <= 5, "the wait counts in the main loop cover two to four slabs in flight");
+
+// wait until at most n of this wave's vector memory operations are outstanding (n known at compile time)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N == 0 || N == 8 || N == 16 || N == 24, "counts used by the slab ring");
+  if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  if (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+}
 
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
 // lds_addr + 16 l (lds_addr is wave-uniform and travels in M0); counted by vmcnt.
@@ -183,8 +193,8 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
       if (s_ < kt_count)
 #pragma unroll
         for (int j = 0; j < 4; ++j) issue_pair(s_, j);
-    if (kt_count < FNST - 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");        // slab 0 landed, two slabs in flight
+    if (kt_count < FNST - 1) wait_vmcnt<0>();
+    else wait_vmcnt<(FNST - 2) * 8>();         // slab 0 landed, the others in flight
     __syncthreads();
 
     // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
@@ -219,11 +229,13 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
       const bool has_next = kt + 1 < kt_count;
       const bool has_load = kt + FNST - 1 < kt_count;
       if (has_next) {
-        // this wave's share of slab kt+1 has landed when at most the loads of slab kt+2 are still
-        // out; the barrier extends that to the other waves' shares, and tells that every wave is
+        // this wave's share of slab kt+1 has landed when at most the loads of the slabs after it are
+        // still out; the barrier extends that to the other waves' shares, and tells that every wave is
         // past its reads of slab kt-1, whose stage the next loads overwrite
-        if (kt + 2 < kt_count) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int rem = kt_count - 2 - kt;     // slabs issued beyond kt+1
+        if (rem >= FNST - 3) wait_vmcnt<(FNST - 3) * 8>();
+        else if (FNST == 5 && rem == 1) wait_vmcnt<8>();
+        else wait_vmcnt<0>();
         __syncthreads();
       }
       const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;

@@ -29,16 +29,15 @@ constexpr int FKT = 16;                            // capacity of the per-thread
 constexpr int FSTG_LD = 65;                        // staging row stride (floats)
 constexpr size_t kFusedLdsBytes = (size_t)FNST * FSTAGE_B;
 static_assert(kFusedLdsBytes >= (size_t)FBM * FSTG_LD * sizeof(float), "staging area must fit");
-static_assert(FNST >= 3 && FNST <= 5, "the wait counts in the main loop cover two to four slabs in flight");
+static_assert(FNST == 4, "the wait counts and the issue order of the main loop are written for this ring");
 
 // wait until at most n of this wave's vector memory operations are outstanding (n known at compile time)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N == 0 || N == 8 || N == 16 || N == 24, "counts used by the slab ring");
+  static_assert(N == 0 || N == 8 || N == 12, "counts used by the slab ring");
   if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  if (N == 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  if (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
@@ -180,21 +179,31 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // k slab s lands in stage s % FNST; every wave issues 4 + 4 loads per slab (pair j = one
-    // 16-row group of each operand)
-    auto issue_pair = [&](int s_, int j) {
-      const unsigned sb = wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024;
-      load_to_lds16(sb, a_ptr[j] + s_ * FBK);
-      load_to_lds16(sb + FBM * FROWB, b_ptr[j] + s_ * FBK);
+    // k slab s lands in stage s % FNST; every wave issues 4 loads per operand and slab (load j = one
+    // 16-row group)
+    auto issue_a = [&](int s_, int j) {
+      load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024, a_ptr[j] + s_ * FBK);
+    };
+    auto issue_b = [&](int s_, int j) {
+      load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + FBM * FROWB + j * 1024, b_ptr[j] + s_ * FBK);
     };
     __syncthreads();                           // previous tile's epilogue no longer reads the staging area
+    // prologue: slabs 0 and 1 and the hidden-state half of slab 2 (its W half follows in the loop)
 #pragma unroll
-    for (int s_ = 0; s_ < FNST - 1; ++s_)
-      if (s_ < kt_count)
+    for (int s_ = 0; s_ < 2; ++s_)
+      if (s_ < kt_count) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) issue_pair(s_, j);
-    if (kt_count < FNST - 1) wait_vmcnt<0>();
-    else wait_vmcnt<(FNST - 2) * 8>();         // slab 0 landed, the others in flight
+        for (int j = 0; j < 4; ++j) issue_a(s_, j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) issue_b(s_, j);
+      }
+    if (2 < kt_count) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) issue_a(2, j);
+      wait_vmcnt<12>();                        // slab 0 landed; slab 1 and half of slab 2 in flight
+    } else {
+      wait_vmcnt<0>();
+    }
     __syncthreads();
 
     // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
@@ -209,15 +218,21 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
       fa[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fa_base + t * 32 * FROWB);
       fb[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fb_base + t * 32 * FROWB);
     }
-    // One k slab: 16 MFMAs per half.  While the first half runs, the fragments of the second half
-    // are read; between the halves the wave makes sure slab kt+1 has landed; while the second half
-    // runs, the loads of slab kt+3 are issued and the first fragments of slab kt+1 are read.  The
-    // LDS and memory instructions sit between the MFMA rows so that the matrix pipe never waits
-    // for their issue.
+    // One k slab: 16 MFMAs per half, as four rows of four.  Between the rows sit one load and two
+    // fragment reads, so that the matrix pipe does not wait for their issue and the 32 loads a
+    // workgroup issues per slab reach the texture path evenly spread:
+    //   first half  : W loads of slab kt+2, fragments of the second half of slab kt
+    //   between     : wait until slab kt+1 has landed, barrier
+    //   second half : hidden-state loads of slab kt+3, first fragments of slab kt+1
     for (int kt = 0; kt < kt_count; ++kt) {
       const unsigned char *sS = ldsb + (kt % FNST) * FSTAGE_B;
+      const bool has_next = kt + 1 < kt_count;
+      const bool load_b = kt + 2 < kt_count;
+      const bool load_a = kt + 3 < kt_count;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        // stage (kt+2) % 4 was last read as slab kt-2: every wave passed the barrier of slab kt-1 after that
+        if (load_b) issue_b(kt + 2, i);
         fa[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fa_base ^ 32) + i * 32 * FROWB);
         fb[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fb_base ^ 32) + i * 32 * FROWB);
         __builtin_amdgcn_sched_barrier(0);
@@ -226,22 +241,18 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      const bool has_next = kt + 1 < kt_count;
-      const bool has_load = kt + FNST - 1 < kt_count;
       if (has_next) {
-        // this wave's share of slab kt+1 has landed when at most the loads of the slabs after it are
-        // still out; the barrier extends that to the other waves' shares, and tells that every wave is
+        // this wave's share of slab kt+1 has landed when at most the 8 loads of slab kt+2 are still
+        // out; the barrier extends that to the other waves' shares, and tells that every wave is
         // past its reads of slab kt-1, whose stage the next loads overwrite
-        const int rem = kt_count - 2 - kt;     // slabs issued beyond kt+1
-        if (rem >= FNST - 3) wait_vmcnt<(FNST - 3) * 8>();
-        else if (FNST == 5 && rem == 1) wait_vmcnt<8>();
+        if (load_b) wait_vmcnt<8>();
         else wait_vmcnt<0>();
         __syncthreads();
       }
       const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        if (has_load) issue_pair(kt + FNST - 1, i);
+        if (load_a) issue_a(kt + 3, i);
         if (has_next) {
           fa[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + i * 32 * FROWB);
           fb[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + i * 32 * FROWB);

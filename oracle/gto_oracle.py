@@ -474,6 +474,59 @@ def max_l_path(tree, node_cum: np.ndarray, d: int):
     return dict(path_len=path_len, path_node=path_node, path_slot=path_slot)
 
 
+def sampled_path(tree, T: np.ndarray, t_lse: np.ndarray, U: np.ndarray, d: int):
+    """Third reading of the "longest accepted sequence" (Sec. 3.2; Sec. 4 evaluates at temperature
+    1 as well): the sequence that lossless verification at temperature 1 accepts.  The tree's
+    children were chosen deterministically (top-k), so each candidate is a point proposal: at the
+    current node, with target distribution p = softmax(target row), the kept children are tried in
+    kept order; child x is accepted with probability p(x) / (1 - mass of the children already
+    rejected at this node), i.e. p renormalised without the rejected tokens.  Acceptance moves to
+    that child, and the walk goes on while the child is itself expanded and depth remains; if
+    every child is rejected the walk ends.  The chance that child x is the one accepted is then
+    exactly p(x), which is what keeps the procedure lossless and makes the expected length equal
+    the node-sum reward of App. A Eq. (2).
+
+    U [R, d, k] holds the uniform numbers in [0, 1): U[r, t, j] decides the j-th child tried at
+    step t (a child is accepted iff U < its acceptance probability).  Outputs as accepted_path,
+    plus `margin` [R]: the smallest |U - acceptance probability| over the decisions taken (a
+    comparison in lower precision can only differ where this is tiny)."""
+    R, g = tree["sel_tok"].shape
+    path_len = np.zeros(R, dtype=np.int32)
+    path_node = np.full((R, d), -1, dtype=np.int32)
+    path_slot = np.full((R, d), -1, dtype=np.int32)
+    margin = np.full(R, np.inf)
+    for r in range(R):
+        n = int(tree["n_sel"][r])
+        cur, slot = -1, 0
+        for t in range(d):
+            rest = 1.0                       # target mass not yet rejected at this node
+            j = 0
+            nxt = -1
+            for i in range(n):
+                if int(tree["sel_parent"][r, i]) != cur or int(tree["sel_depth"][r, i]) != t + 1:
+                    continue
+                tok = int(tree["sel_tok"][r, i])
+                p_tok = math.exp(float(T[r, t, slot, tok]) - float(t_lse[r, t, slot]))
+                acc = p_tok / rest if rest > 0.0 else 1.0
+                u = float(U[r, t, j])
+                margin[r] = min(margin[r], abs(u - acc))
+                if u < acc:
+                    nxt = i
+                    break
+                rest -= p_tok
+                j += 1
+            if nxt < 0:
+                break
+            path_node[r, t] = nxt
+            path_slot[r, t] = slot
+            path_len[r] = t + 1
+            own = int(tree["sel_slot"][r, nxt])
+            if own < 0:
+                break
+            cur, slot = nxt, own
+    return dict(path_len=path_len, path_node=path_node, path_slot=path_slot, margin=margin)
+
+
 # ---------------------------------------------------------------------- advantage
 def group_advantage(r_cur, r_ref, m: int, delta: float = 1e-6):
     """Eq. 9-10: debias against the reference tree, then standardise inside each
@@ -598,18 +651,24 @@ def token_loss(D: np.ndarray, T: np.ndarray, weight=None, grad_scale: float = 1.
 
 # ------------------------------------------------------------------------ whole path
 def full_path(D_cur, T_cur, D_ref, T_ref, *, k, d, g, m, eta=1.0, eps=0.2, delta=1e-6,
-              grad_scale=1.0, reward_mode="lse", want_grad=True, logit_err=0.0, path_mode="greedy"):
+              grad_scale=1.0, reward_mode="lse", want_grad=True, logit_err=0.0, path_mode="greedy", U_cur=None,
+              U_ref=None):
     """Algorithm 1, lines for one minibatch of R roots, composed from the steps
     above.  D_ref doubles as the reference model's logits at the current tree's
     slot coordinates (Eq. 11 denominator)."""
     out = {}
-    for tag, D, T in (("cur", D_cur, T_cur), ("ref", D_ref, T_ref)):
+    for tag, D, T, U in (("cur", D_cur, T_cur, U_cur), ("ref", D_ref, T_ref, U_ref)):
         ds = draft_row_stats(D, k)
         pool = expand_tree(ds["top_tok"], ds["top_logp32"], d, k, ds["top_logp64"], ds["top_logit"], logit_err)
         tree = select_topg(pool, g, audit=True)
         ts = target_row_stats(T)
         rew = tree_reward(tree, T, ts["t_lse"], eta)
-        path = accepted_path(tree, ts["t_argmax"], d) if path_mode == "greedy" else max_l_path(tree, rew["node_cum"], d)
+        if path_mode == "greedy":
+            path = accepted_path(tree, ts["t_argmax"], d)
+        elif path_mode == "max_l":
+            path = max_l_path(tree, rew["node_cum"], d)
+        else:
+            path = sampled_path(tree, T, ts["t_lse"], U, d)
         out[tag] = dict(dstats=ds, pool=pool, tree=tree, tstats=ts, reward=rew, path=path)
     key = "reward_" + reward_mode
     adv = group_advantage(out["cur"]["reward"][key], out["ref"]["reward"][key], m, delta)

@@ -174,3 +174,110 @@ def test_max_l_path_is_the_branch_with_the_largest_expected_length():
         for t in range(l):
             assert expanded[winners[0][:t]] == (t, int(path["path_slot"][r, t]))
         assert (path["path_node"][r, l:] == -1).all() and (path["path_slot"][r, l:] == -1).all()
+
+
+# ----------------------------------------------------------------- sampled (temperature 1) walk
+def _children(tree, r, parent, depth):
+    n = int(tree["n_sel"][r])
+    return [i for i in range(n) if tree["sel_parent"][r, i] == parent and tree["sel_depth"][r, i] == depth]
+
+
+def test_sampled_walk_accepts_each_child_with_its_target_probability():
+    """Lossless verification: whatever the order of the candidates, the chance that child x is the
+    one accepted at a node equals the target probability p(x).  The oracle's acceptance thresholds
+    a_1, a_2, ... are found by bisection on the uniform number of each trial (earlier trials forced
+    to reject), and prod_{i<j} (1 - a_i) * a_j is compared with scipy's softmax."""
+    D, T, pool, tree, ts = _case(7, 1, 3, 3, 12, 10, sigma=1.0)
+    d, k = 3, 3
+
+    def thresholds(prefix_u, t, parent):
+        kids = _children(tree, 0, parent, t + 1)
+        out = []
+        for j, kid in enumerate(kids):
+            lo, hi = 0.0, 1.0
+            for _ in range(60):
+                mid = 0.5 * (lo + hi)
+                U = np.array(prefix_u, dtype=np.float64).copy()
+                U[0, t, :j] = 1.0 - 1e-12          # reject the earlier candidates
+                U[0, t, j] = mid
+                got = O.sampled_path(tree, T, ts["t_lse"], U, d)
+                if got["path_len"][0] > t and got["path_node"][0, t] == kid:
+                    lo = mid                       # accepted: the threshold is above mid
+                else:
+                    hi = mid
+            out.append(0.5 * (lo + hi))
+        return kids, out
+
+    U0 = np.zeros((1, d, k))
+    kids, a = thresholds(U0, 0, -1)
+    assert len(kids) >= 2
+    p = sp.softmax(T[0, 0, 0])
+    keep = 1.0
+    for kid, aj in zip(kids, a):
+        assert abs(keep * aj - p[tree["sel_tok"][0, kid]]) < 1e-9
+        keep *= 1.0 - aj
+    # one level down, below the first child (accepted by U = 0 at step 0)
+    first = kids[0]
+    slot = int(tree["sel_slot"][0, first])
+    assert slot >= 0
+    kids1, a1 = thresholds(U0, 1, first)
+    assert len(kids1) >= 1
+    p1 = sp.softmax(T[0, 1, slot])
+    keep = 1.0
+    for kid, aj in zip(kids1, a1):
+        assert abs(keep * aj - p1[tree["sel_tok"][0, kid]]) < 1e-9
+        keep *= 1.0 - aj
+
+
+def test_sampled_walk_mean_length_is_the_nodesum_reward():
+    """App. A Eq. (2): the expected number of accepted tokens is the sum over kept nodes of the
+    probability that the node is reached; checked by Monte Carlo over the uniform numbers."""
+    D, T, pool, tree, ts = _case(5, 1, 3, 3, 12, 10, sigma=1.0)
+    rew = O.tree_reward(tree, T, ts["t_lse"], 1.0)
+    n = 40000
+    rep = {key: np.repeat(val, n, axis=0) for key, val in tree.items() if isinstance(val, np.ndarray) and val.shape[:1] == (1,)}
+    Tn = np.broadcast_to(T, (n,) + T.shape[1:])
+    lse_n = np.broadcast_to(ts["t_lse"], (n,) + ts["t_lse"].shape[1:])
+    U = np.random.default_rng(123).random((n, 3, 3))
+    got = O.sampled_path(rep, Tn, lse_n, U, 3)
+    lens = got["path_len"].astype(np.float64)
+    sigma = lens.std() / math.sqrt(n)
+    assert abs(lens.mean() - rew["reward_nodesum"][0]) < 4 * sigma + 1e-12
+    # first step: frequency of each depth-1 node against its target probability
+    p = sp.softmax(T[0, 0, 0])
+    for kid in _children(tree, 0, -1, 1):
+        freq = np.mean((got["path_len"] > 0) & (got["path_node"][:, 0] == kid))
+        pk = p[tree["sel_tok"][0, kid]]
+        assert abs(freq - pk) < 4 * math.sqrt(pk * (1 - pk) / n) + 1e-12
+
+
+def test_sampled_walk_special_cases():
+    D, T, pool, tree, ts = _case(33, 6, 4, 3, 8, 20, sigma=2.5)
+    d, k = 4, 3
+    # U = 0 accepts the first candidate at every node: the chain of first children in kept order
+    got = O.sampled_path(tree, T, ts["t_lse"], np.zeros((6, d, k)), d)
+    for r in range(6):
+        cur, t = -1, 0
+        while t < d:
+            kids = _children(tree, r, cur, t + 1)
+            if not kids:
+                break
+            assert got["path_node"][r, t] == kids[0]
+            cur = kids[0]
+            t += 1
+            if tree["sel_slot"][r, cur] < 0:
+                break
+        assert got["path_len"][r] == t
+    # a target that puts (almost) all mass on one token makes the walk the greedy walk for any U
+    T2 = T.copy()
+    am = ts["t_argmax"]
+    for r in range(6):
+        for t in range(d):
+            for j in range(k):
+                T2[r, t, j, am[r, t, j]] += 80.0
+    ts2 = O.target_row_stats(T2)
+    U = np.random.default_rng(4).random((6, d, k)) * 0.999
+    a = O.sampled_path(tree, T2, ts2["t_lse"], U, d)
+    b = O.accepted_path(tree, ts2["t_argmax"], d)
+    for key in ("path_len", "path_node", "path_slot"):
+        assert (a[key] == b[key]).all()

@@ -189,6 +189,18 @@ def block_roots(w: Workload) -> int:
     return max(1, min(w.R, (2 << 30) // per_root))
 
 
+def make_uniforms(w, device, seed_offset: int = 0) -> Dict[str, torch.Tensor]:
+    """Uniform numbers in [0, 1) for the temperature-1 verification walk: one fp32 [R, d, k] tensor per
+    tree ("cur", "ref"), drawn from the workload's seed (+ 7919 + seed_offset) on the CPU so that the
+    bits do not depend on the device."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(w.seed + 7919 + seed_offset)
+    out = {}
+    for tag in ("cur", "ref"):
+        out[tag] = torch.rand((w.R, w.d, w.k), generator=gen, dtype=torch.float32).to(device)
+    return out
+
+
 def make_logits(w: Workload, device, want=("D_cur", "T_cur", "D_ref", "T_ref"),
                 roots: Optional[range] = None) -> Dict[str, torch.Tensor]:
     """Generate the requested tensors for `roots` (default: all R roots) on

@@ -53,8 +53,13 @@ typedef enum gto_status {
 
 enum { GTO_BF16 = 0, GTO_F32 = 1 };
 /* Longest accepted sequence (Sec. 3.2): GREEDY = the sequence greedy (T = 0) target verification
- * accepts (default); MAX_L = the root-to-leaf sequence with the largest expected acceptance length. */
-enum { GTO_PATH_GREEDY = 0, GTO_PATH_MAX_L = 1 };
+ * accepts (default); MAX_L = the root-to-leaf sequence with the largest expected acceptance length;
+ * SAMPLED = the sequence lossless verification at temperature 1 accepts (Sec. 4 evaluates at T = 1
+ * too): at each node the kept children are tried in kept order, child x being accepted with
+ * probability p_T(x) / (1 - target mass of the children already rejected at that node), decided by
+ * the caller's uniform numbers gto_reward.accept_u (child x ends up accepted with probability
+ * p_T(x), so the expected length is the node-sum reward of App. A Eq. (2)). */
+enum { GTO_PATH_GREEDY = 0, GTO_PATH_MAX_L = 1, GTO_PATH_SAMPLED = 2 };
 enum { GTO_REWARD_LSE = 0, GTO_REWARD_MAX = 1, GTO_REWARD_MEAN = 2, GTO_REWARD_NODESUM = 3 };
 enum {
   GTO_FLAG_GRAD_ZERO_FILL = 1, /* bwd also writes zeros into rows that carry no gradient                */
@@ -125,6 +130,9 @@ typedef struct gto_reward {
   int32_t *path_len;   /* [R]    length l of the longest accepted sequence, 0..d            */
   int32_t *path_node;  /* [R, d] its nodes as positions in the kept list, -1 beyond l       */
   int32_t *path_slot;  /* [R, d] slot (within level t) of the node whose row produced step t */
+  const float *accept_u; /* in, [R, d, k]: uniform numbers in [0, 1) for GTO_PATH_SAMPLED; entry (r, t, j)
+                            decides the j-th child tried at step t.  Not read (may be NULL) in the other
+                            path modes; GTO_E_NULL if it is NULL in that mode.                          */
 } gto_reward;
 
 typedef struct gto_ppo {

@@ -6,7 +6,7 @@ if the library is missing, importing the binding's entry points raises.
 """
 from .binding import (  # noqa: F401
     GTO_BF16, GTO_F32, GTO_REWARD_LSE, GTO_REWARD_MAX, GTO_REWARD_MEAN, GTO_REWARD_NODESUM,
-    GTO_FLAG_GRAD_ZERO_FILL, GTO_FLAG_TARGET_PRUNE, GTO_PATH_GREEDY, GTO_PATH_MAX_L, GtoError, make_config, lib, lib_path,
+    GTO_FLAG_GRAD_ZERO_FILL, GTO_FLAG_TARGET_PRUNE, GTO_PATH_GREEDY, GTO_PATH_MAX_L, GTO_PATH_SAMPLED, GtoError, make_config, lib, lib_path,
     alloc_draft_stats, alloc_target_stats, alloc_pool, alloc_tree, alloc_reward, alloc_ppo,
     gto_version, gto_strerror, gto_workspace_bytes,
     gto_draft_row_stats, gto_target_row_stats, gto_expand_tree, gto_expand_from_stats,

@@ -9,7 +9,7 @@ import torch
 
 GTO_BF16, GTO_F32 = 0, 1
 GTO_REWARD_LSE, GTO_REWARD_MAX, GTO_REWARD_MEAN, GTO_REWARD_NODESUM = 0, 1, 2, 3
-GTO_PATH_GREEDY, GTO_PATH_MAX_L = 0, 1
+GTO_PATH_GREEDY, GTO_PATH_MAX_L, GTO_PATH_SAMPLED = 0, 1, 2
 GTO_FLAG_GRAD_ZERO_FILL = 1
 GTO_FLAG_TARGET_PRUNE = 2
 
@@ -48,7 +48,8 @@ _TARGET = ("t_max", "t_lse", "t_argmax")
 _POOL = ("cand_tok", "cand_parent", "cand_depth", "cand_pslot", "cand_slot", "cand_score", "slot_cand")
 _TREE = ("sel_cand", "sel_tok", "sel_parent", "sel_depth", "sel_pslot", "sel_slot", "sel_leaf", "sel_score", "n_sel",
          "slot_need")
-_REWARD = ("node_q", "node_cum", "reward", "reward_aux", "n_leaves", "path_len", "path_node", "path_slot")
+_REWARD = ("node_q", "node_cum", "reward", "reward_aux", "n_leaves", "path_len", "path_node", "path_slot",
+           "accept_u")   # accept_u: optional input of the sampled walk, put into the dict by the caller
 _PPO = ("logM", "logM0", "ratio", "term", "active", "coef", "loss_group", "loss")
 gto_draft_stats = _ptr_struct("gto_draft_stats", _DRAFT)
 gto_target_stats = _ptr_struct("gto_target_stats", _TARGET)

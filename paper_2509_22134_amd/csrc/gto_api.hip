@@ -64,7 +64,8 @@ int check_cfg(const gto_config *c, bool need_group) {
   if ((c->row_stride * elem_size(c->dtype)) % 16 != 0) return GTO_E_ALIGN;
   if (c->reward_mode < GTO_REWARD_LSE || c->reward_mode > GTO_REWARD_NODESUM) return GTO_E_MODE;
   if (!(c->eta > 0.f) || !(c->eps >= 0.f) || !(c->delta >= 0.f)) return GTO_E_MODE;
-  if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L) return GTO_E_MODE;
+  if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L && c->path_mode != GTO_PATH_SAMPLED)
+    return GTO_E_MODE;
   if (need_group && (c->group_size < 1 || c->R % c->group_size != 0)) return GTO_E_SHAPE;
   return GTO_OK;
 }
@@ -116,6 +117,12 @@ int check_reward(const gto_reward *w) {
     return GTO_E_NULL;
   return GTO_OK;
 }
+// the entry points that take the verification walk also need the uniform numbers in the sampled mode
+int check_reward_out(const gto_config *c, const gto_reward *w) {
+  GTO_TRY(check_reward(w));
+  if (c->path_mode == GTO_PATH_SAMPLED && w->accept_u == nullptr) return GTO_E_NULL;
+  return GTO_OK;
+}
 int check_ppo(const gto_ppo *p) {
   if (!p || any_null({p->logM, p->logM0, p->ratio, p->term, p->active, p->coef, p->loss_group, p->loss}))
     return GTO_E_NULL;
@@ -164,7 +171,7 @@ void run_reward(const gto_config *c, const gto_tree *t, const void *logits, cons
   a.R = c->R; a.d = c->d; a.k = c->k; a.g = c->g; a.dtype = c->dtype; a.reward_mode = c->reward_mode;
   a.path_mode = c->path_mode;
   a.row_stride = c->row_stride; a.eta = c->eta;
-  a.target_logits = logits; a.t_lse = s->t_lse; a.t_argmax = s->t_argmax;
+  a.target_logits = logits; a.t_lse = s->t_lse; a.t_argmax = s->t_argmax; a.accept_u = w->accept_u;
   a.sel_tok = t->sel_tok; a.sel_parent = t->sel_parent; a.sel_depth = t->sel_depth;
   a.sel_pslot = t->sel_pslot; a.sel_slot = t->sel_slot; a.sel_leaf = t->sel_leaf; a.n_sel = t->n_sel;
   a.node_q = w->node_q; a.node_cum = w->node_cum; a.reward = w->reward; a.reward_aux = w->reward_aux;
@@ -392,7 +399,7 @@ int gto_reward_from_stats(const gto_config *cfg, const gto_tree *tree, const voi
   GTO_TRY(check_logits(target_logits));
   GTO_TRY(check_tree(tree));
   GTO_TRY(check_target_stats(stats));
-  GTO_TRY(check_reward(reward_out));
+  GTO_TRY(check_reward_out(cfg, reward_out));
   run_reward(cfg, tree, target_logits, stats, reward_out, (hipStream_t)hip_stream);
   return hip_status();
 }
@@ -406,7 +413,7 @@ int gto_tree_reward(const gto_config *cfg, const gto_tree *tree, const void *tar
   GTO_TRY(check_logits(target_logits));
   GTO_TRY(check_tree(tree));
   GTO_TRY(check_target_stats(stats_out));
-  GTO_TRY(check_reward(reward_out));
+  GTO_TRY(check_reward_out(cfg, reward_out));
   run_target_rows(cfg, target_logits, stats_out,
                   (cfg->flags & GTO_FLAG_TARGET_PRUNE) ? tree->slot_need : nullptr, (hipStream_t)hip_stream);
   run_reward(cfg, tree, target_logits, stats_out, reward_out, (hipStream_t)hip_stream);
@@ -552,7 +559,7 @@ int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const voi
   GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_target_vh));
   GTO_TRY(check_tree(tree));
   GTO_TRY(check_target_stats(stats_out));
-  GTO_TRY(check_reward(reward_out));
+  GTO_TRY(check_reward_out(cfg, reward_out));
   const FusedWs L = fused_ws(cfg);
   GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
   hipStream_t st = (hipStream_t)hip_stream;
@@ -577,6 +584,7 @@ int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const voi
     a.path_mode = cfg->path_mode;
     a.row_stride = 0; a.eta = cfg->eta;
     a.target_logits = nullptr; a.node_logit = node_logit; a.t_lse = stats_out->t_lse; a.t_argmax = stats_out->t_argmax;
+    a.accept_u = reward_out->accept_u;
     a.sel_tok = tree->sel_tok; a.sel_parent = tree->sel_parent; a.sel_depth = tree->sel_depth;
     a.sel_pslot = tree->sel_pslot; a.sel_slot = tree->sel_slot; a.sel_leaf = tree->sel_leaf; a.n_sel = tree->n_sel;
     a.node_q = reward_out->node_q; a.node_cum = reward_out->node_cum; a.reward = reward_out->reward;

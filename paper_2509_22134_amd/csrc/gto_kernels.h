@@ -54,6 +54,7 @@ struct RewardArgs {
   const float *node_logit;   // optional [R, g]: logits of the kept tokens gathered beforehand (fused variant)
   const float *t_lse;
   const int32_t *t_argmax;
+  const float *accept_u;     // [R, d, k] uniform numbers of the sampled walk (path_mode 2 only)
   const int32_t *sel_tok, *sel_parent, *sel_depth, *sel_pslot, *sel_slot, *sel_leaf, *n_sel;
   float *node_q, *node_cum, *reward, *reward_aux;
   int32_t *n_leaves, *path_len, *path_node, *path_slot;

@@ -268,6 +268,42 @@ __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
     }
     return;
   }
+  if (a.path_mode == 2) {
+    // verification at temperature 1: the kept children of the current node are tried in kept order,
+    // child x accepted with probability p_T(x) / (target mass not yet rejected at this node), decided
+    // by the caller's uniform numbers; s_logt still holds log p_T of every kept token
+    __syncthreads();
+    if (tid == 0) {
+      int cur = -1, slot = 0, len = 0;
+      for (int t = 0; t < d; ++t) {
+        double rest = 1.0;
+        int j = 0, nxt = -1;
+        for (int i = 0; i < n; ++i) {
+          if (s_parent[i] != cur || a.sel_depth[sel0 + i] != t + 1) continue;
+          const double p_tok = exp(s_logt[i]);
+          const double acc = (rest > 0.0) ? p_tok / rest : 1.0;
+          const double u = (double)a.accept_u[((int64_t)r * d + t) * k + j];
+          if (u < acc) { nxt = i; break; }
+          rest -= p_tok;
+          ++j;
+        }
+        if (nxt < 0) break;
+        a.path_node[(int64_t)r * d + t] = nxt;
+        a.path_slot[(int64_t)r * d + t] = slot;
+        len = t + 1;
+        const int own = a.sel_slot[sel0 + nxt];
+        if (own < 0) break;
+        cur = nxt;
+        slot = own;
+      }
+      for (int t = len; t < d; ++t) {
+        a.path_node[(int64_t)r * d + t] = -1;
+        a.path_slot[(int64_t)r * d + t] = -1;
+      }
+      a.path_len[r] = len;
+    }
+    return;
+  }
   // greedy verification walk (T = 0): follow the kept child that equals the target argmax
   int cur = -1, slot = 0, len = 0;
   bool alive = true;

@@ -45,7 +45,13 @@ class GtoPath:
         B.gto_tree_reward(self.cfg, b["tree"], T, b["tstats"], b["reward"])
 
     def step(self, D_cur, T_cur, D_ref: Optional[torch.Tensor] = None, T_ref: Optional[torch.Tensor] = None,
-             ref_stats_known: bool = True):
+             ref_stats_known: bool = True, accept_u: Optional[Dict[str, torch.Tensor]] = None):
+        """accept_u: {"cur": [R, d, k] fp32, "ref": ...} uniform numbers, needed by GTO_PATH_SAMPLED only."""
+        for tag in self.buf:
+            if accept_u:
+                self.buf[tag]["reward"]["accept_u"] = accept_u[tag]
+            else:
+                self.buf[tag]["reward"].pop("accept_u", None)
         self.build_and_score("cur", D_cur, T_cur)
         if not self.full_path:
             return
@@ -65,10 +71,10 @@ class GtoFusedPath:
     (draft head for both draft models, target head for the target)."""
 
     def __init__(self, *, R, d, k, g, V, hidden, group_size, device, eta=1.0, eps=0.2, delta=1e-6,
-                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True):
+                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0):
         self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=B.GTO_BF16, group_size=group_size,
                                  reward_mode=reward_mode, eta=eta, eps=eps, delta=delta, grad_scale=grad_scale,
-                                 flags=flags)
+                                 flags=flags, path_mode=path_mode)
         self.hidden = hidden
         self.want_grad = want_grad
         self.buf = {}
@@ -89,7 +95,12 @@ class GtoFusedPath:
         B.gto_select_topg(self.cfg, b["pool"], b["tree"])
         B.gto_tree_reward_fused(self.cfg, b["tree"], H, W_target, b["tstats"], b["reward"], self.workspace)
 
-    def step(self, H_cur, H_ref, W_draft, W_target):
+    def step(self, H_cur, H_ref, W_draft, W_target, accept_u=None):
+        for tag in self.buf:
+            if accept_u:
+                self.buf[tag]["reward"]["accept_u"] = accept_u[tag]
+            else:
+                self.buf[tag]["reward"].pop("accept_u", None)
         self.build_and_score("cur", H_cur, W_draft, W_target)
         self.build_and_score("ref", H_ref, W_draft, W_target)
         cur, ref = self.buf["cur"], self.buf["ref"]

@@ -8,7 +8,7 @@ TAU = 1.0           # oracle's gap-to-error-budget ratio below which a ranking d
 
 
 def to_np(d):
-    return {k: v.detach().cpu().numpy() for k, v in d.items()}
+    return {k: v.detach().cpu().numpy() for k, v in d.items() if v is not None}
 
 
 def logits_np(t) -> np.ndarray:

@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     assert C.sizeof(B.gto_config) == 64
     assert B.gto_config.row_stride.offset == 24
-    assert C.sizeof(B.gto_tree) == 10 * 8 and C.sizeof(B.gto_reward) == 8 * 8
+    assert C.sizeof(B.gto_tree) == 10 * 8 and C.sizeof(B.gto_reward) == 9 * 8
 
 
 def _cfg(**kw):
@@ -92,6 +92,10 @@ def test_validation_errors_without_gpu():
     assert _status(G.gto_group_advantage, _cfg(), None, fake, fake) == E["null"]
     assert _status(G.gto_select_topg, _cfg(), None, fd) == E["null"]
     assert _status(G.gto_tree_reward, _cfg(), fd, None, fd, fd) == E["null"]
+    assert _status(G.gto_tree_reward, _cfg(path_mode=3), fd, fake, fd, fd) == E["mode"]
+    # the temperature-1 walk needs the caller's uniform numbers
+    no_u = {n: fake for n in B._REWARD if n != "accept_u"}
+    assert _status(G.gto_tree_reward, _cfg(path_mode=G.GTO_PATH_SAMPLED), fd, fake, fd, no_u) == E["null"]
     # surrogate forward without reference statistics needs a workspace
     assert _status(G.gto_ppo_surrogate_fwd, _cfg(), fd, fd, fake, fd, fake, None, fake, fd) == E["ws"]
     assert "workspace" in G.gto_strerror(E["ws"])

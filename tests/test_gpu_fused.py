@@ -108,6 +108,35 @@ def test_fused_full_path_matches_oracle(gpu_device, R, d, k, g, hidden, V, corr)
     assert n_ambig <= R            # of 2 R trees
 
 
+def test_fused_sampled_walk(gpu_device):
+    _say("fused: temperature-1 verification walk")
+    w = S.FusedWorkload("case", R=24, V=3000, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    t = S.make_fused(w, gpu_device)
+    un = S.make_uniforms(w, gpu_device)
+    path = GtoFusedPath(R=w.R, d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m, device=gpu_device,
+                        eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, path_mode=G.GTO_PATH_SAMPLED)
+    path.grad_rows.fill_(7.0)
+    path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"], accept_u=un)
+    torch.cuda.synchronize()
+    L = _oracle_logits(t, list(range(w.R)))
+    E = logit_error_bound(w.hidden, max(float(np.abs(v).max()) for v in L.values()))
+    total = 0
+    for tag in ("cur", "ref"):
+        b = path.buf[tag]
+        gd, gt, grew = U.to_np(b["dstats"]), U.to_np(b["tstats"]), U.to_np(b["reward"])
+        _, tree2, _, _ = U.oracle_from_gpu_stats(gd, gt, L["T_" + tag], w.d, w.k, w.g, w.eta)
+        path2 = O.sampled_path(tree2, L["T_" + tag], gt["t_lse"].astype(np.float64),
+                               un[tag].cpu().numpy().astype(np.float64), w.d)
+        sure = path2["margin"] > 8 * E + 1e-6          # the GPU's token logits differ from the oracle's by up to E
+        for n in U.INT_PATH:
+            assert np.array_equal(grew[n][sure], path2[n][sure]), (tag, n)
+        assert sure.sum() >= w.R - 2
+        total += int(grew["path_len"].sum())
+    assert total > 0
+    _compare_ppo(w, L, path)
+
+
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     _say("fused: chunk count / workgroup layout invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,

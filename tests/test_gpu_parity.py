@@ -290,6 +290,46 @@ def test_max_l_reading_of_the_longest_accepted_sequence(gpu_device):
     _compare_ppo(w, tens, path)
 
 
+@pytest.mark.parametrize("name,R,V", [("tiny", 64, None), ("llama31_8b", 16, 12000)])
+def test_sampled_reading_of_the_longest_accepted_sequence(gpu_device, name, R, V):
+    _say(f"path mode: temperature-1 verification, {name}")
+    w = S.scaled(S.CONFIGS[name], R=R, V=V or S.CONFIGS[name].V)
+    tens = S.make_logits(w, gpu_device)
+    un = S.make_uniforms(w, gpu_device)
+    path = GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=gpu_device,
+                   eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, path_mode=G.GTO_PATH_SAMPLED)
+    path.grad_rows.fill_(7.0)
+    path.step(tens["D_cur"], tens["T_cur"], tens["D_ref"], tens["T_ref"], accept_u=un)
+    torch.cuda.synchronize()
+    sub = {n: U.logits_np(t) for n, t in tens.items()}
+    un_np = {tag: t.cpu().numpy().astype(np.float64) for tag, t in un.items()}
+    ora = O.full_path(sub["D_cur"], sub["T_cur"], sub["D_ref"], sub["T_ref"], k=w.k, d=w.d, g=w.g, m=w.m, eta=w.eta,
+                      eps=w.eps, delta=w.delta, want_grad=False, path_mode="sampled", U_cur=un_np["cur"],
+                      U_ref=un_np["ref"])
+    n_clear = 0
+    lens = []
+    for tag in ("cur", "ref"):
+        b = path.buf[tag]
+        gd, gt, grew = U.to_np(b["dstats"]), U.to_np(b["tstats"]), U.to_np(b["reward"])
+        # the oracle's walk on the GPU's own fp32 statistics: every decision compares the same numbers
+        pool2, tree2, rew2, _ = U.oracle_from_gpu_stats(gd, gt, sub["T_" + tag], w.d, w.k, w.g, w.eta)
+        path2 = O.sampled_path(tree2, sub["T_" + tag], gt["t_lse"].astype(np.float64), un_np[tag], w.d)
+        sure = path2["margin"] > 1e-9
+        for n in U.INT_PATH:
+            assert np.array_equal(grew[n][sure], path2[n][sure]), (tag, n)
+        assert sure.sum() >= R - 1
+        # against the pure fp64 oracle where neither the tree nor a decision is a near tie
+        o = ora[tag]
+        clear = (np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"]) >= U.TAU) & (o["path"]["margin"] > 1e-5)
+        for n in U.INT_PATH:
+            assert np.array_equal(grew[n][clear], o["path"][n][clear]), (tag, n)
+        n_clear += int(clear.sum())
+        lens.append(grew["path_len"])
+    assert n_clear >= R                                   # most roots of both trees are compared end to end
+    assert np.concatenate(lens).max() >= 1                # some walks accept something
+    _compare_ppo(w, tens, path)
+
+
 def test_bitwise_deterministic(gpu_device):
     _say("determinism")
     w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=16000)

@@ -119,6 +119,8 @@ def main():
                     help="stream every used target row instead of only those the kept tree refers to")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel (4 GiB) so that HBM counters can be scaled")
+    ap.add_argument("--group-size", type=int, default=0, help="override m, the roots per advantage group (0 = workload's)")
+    ap.add_argument("--one-stream", action="store_true", help="chunked workloads: issue every chunk on one stream")
     ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -142,6 +144,8 @@ def main():
     w = S.CONFIGS[args.workload]
     if args.roots:
         w = S.scaled(w, R=args.roots)
+    if args.group_size:
+        w = S.scaled(w, m=args.group_size)
     if args.waves:
         G.gto_set_waves_per_row(args.waves)
     R = w.chunk_roots or w.R
@@ -149,13 +153,29 @@ def main():
     wr = S.scaled(w, R=R)
     want = ("D_cur", "T_cur", "D_ref", "T_ref") if w.full_path else ("D_cur", "T_cur")
     tens = S.make_logits(wr, dev, want=want)        # one chunk resident; chunks reuse the buffers
-    path = GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=dev,
-                   eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path,
-                   flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE)
+    # a chunked workload alternates its chunks between two streams (each with its own buffers), so that the
+    # short per-root kernels of one chunk run under the row streaming of the next
+    n_lanes = 2 if (n_chunks > 1 and not args.one_stream) else 1
+    paths = [GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=dev,
+                     eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path,
+                     flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE) for _ in range(n_lanes)]
+    path = paths[0]
+    streams = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if n_lanes > 1 else [None]
 
     def step():
-        for _ in range(n_chunks):
-            path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
+        if n_lanes == 1:
+            for _ in range(n_chunks):
+                path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
+            return
+        start = torch.cuda.current_stream().record_event()
+        for c in range(n_chunks):
+            st = streams[c % n_lanes]
+            if c < n_lanes:
+                st.wait_event(start)
+            with torch.cuda.stream(st):
+                paths[c % n_lanes].step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
+        for st in streams:
+            torch.cuda.current_stream().wait_stream(st)
 
     for _ in range(args.warmup):
         step()
@@ -167,13 +187,21 @@ def main():
             G.gto_calibration_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
-    G.gto_profile_enable(True)
+    G.gto_profile_enable(n_lanes == 1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     G.gto_profile_enable(False)
+    if n_lanes > 1:
+        # kernels of the two streams overlap in the timed region, so their own durations are taken from one
+        # more pass that issues every chunk on one stream
+        G.gto_profile_enable(True)
+        for _ in range(n_chunks):
+            path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
+        torch.cuda.synchronize()
+        G.gto_profile_enable(False)
     prof = G.gto_profile_read()
 
     trees_per_step = w.R * (2 if w.full_path else 1)
@@ -205,7 +233,9 @@ def main():
         "config": {"workload": f"{w.name}: R={w.R} V={w.V} k={w.k} d={w.d} g={w.g} m={w.m} "
                                f"{w.dtype} logits, " + ("full path, current + reference tree per root"
                                                        if w.full_path else "reward only"),
-                   "chunks": n_chunks, "waves_per_row": args.waves or "auto",
+                   "chunks": n_chunks, "streams": n_lanes,
+                   "kernel_durations": "timed region" if n_lanes == 1 else "separate one-stream pass after the timed region",
+                   "waves_per_row": args.waves or "auto",
                    "target_rows": "all used slots" if args.no_prune else "only slots with a kept child",
                    "target_rows_streamed_per_chunk": target_rows, "draft_rows_per_chunk": n_models * R * w.rho},
         "logit_gb_s": fwd_bytes / (dt / args.steps) / 1e9,

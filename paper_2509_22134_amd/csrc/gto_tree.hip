@@ -345,29 +345,28 @@ void launch_reward(const RewardArgs &a, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------ advantage
-__global__ void k_advantage(AdvArgs a) {
-  const int grp = blockIdx.x * blockDim.x + threadIdx.x;
-  if (grp >= a.R / a.m) return;
+// One wave per group: lane-strided fp64 sums and a fixed-shape wave reduction (deterministic for any m).
+__global__ __launch_bounds__(64) void k_advantage(AdvArgs a) {
+  const int grp = blockIdx.x, lane = threadIdx.x;
   const int i0 = grp * a.m;
   double sum = 0.0;
-  for (int i = 0; i < a.m; ++i)
+  for (int i = lane; i < a.m; i += 64)
     sum += (double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0);
-  const double mean = sum / a.m;
+  const double mean = wave_sum(sum) / a.m;
   double var = 0.0;
-  for (int i = 0; i < a.m; ++i) {
+  for (int i = lane; i < a.m; i += 64) {
     const double dv = ((double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0)) - mean;
     var += dv * dv;
   }
-  const double sd = sqrt(var / a.m);
-  for (int i = 0; i < a.m; ++i) {
+  const double sd = sqrt(wave_sum(var) / a.m);
+  for (int i = lane; i < a.m; i += 64) {
     const double dv = ((double)a.r_cur[i0 + i] - (a.r_ref ? (double)a.r_ref[i0 + i] : 0.0)) - mean;
     a.adv[i0 + i] = (float)(dv / (sd + (double)a.delta));
   }
 }
 
 void launch_advantage(const AdvArgs &a, hipStream_t st) {
-  const int groups = a.R / a.m;
-  hipLaunchKernelGGL(k_advantage, dim3((groups + 63) / 64), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(k_advantage, dim3(a.R / a.m), dim3(64), 0, st, a);
 }
 
 // ------------------------------------------------------------------------------ surrogate fwd
@@ -409,16 +408,31 @@ __global__ void k_ppo_root(PpoFwdArgs a) {
 }
 
 __global__ __launch_bounds__(256) void k_ppo_loss(PpoFwdArgs a) {
-  // single block: group losses, then their mean with a fixed-shape tree reduction
+  // single block: group losses (Eq. 12), then their mean; every sum has a fixed shape
   const int K = a.R / a.m;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __shared__ double s_red[256];
   double part = 0.0;
-  for (int grp = threadIdx.x; grp < K; grp += 256) {
-    double sum = 0.0;
-    for (int i = 0; i < a.m; ++i) sum += (double)a.term[grp * a.m + i];
-    const double lg = -sum / a.m;
-    a.loss_group[grp] = (float)lg;
-    part += lg;
+  if (a.m <= 16) {
+    // small groups: one thread per group
+    for (int grp = threadIdx.x; grp < K; grp += 256) {
+      double sum = 0.0;
+      for (int i = 0; i < a.m; ++i) sum += (double)a.term[grp * a.m + i];
+      const double lg = -sum / a.m;
+      a.loss_group[grp] = (float)lg;
+      part += lg;
+    }
+  } else {
+    // large groups: one wave per group, lane-strided sum and wave reduction
+    for (int grp = wave; grp < K; grp += 4) {
+      double sum = 0.0;
+      for (int i = lane; i < a.m; i += 64) sum += (double)a.term[grp * a.m + i];
+      const double lg = -wave_sum(sum) / a.m;
+      if (lane == 0) {
+        a.loss_group[grp] = (float)lg;
+        part += lg;
+      }
+    }
   }
   s_red[threadIdx.x] = part;
   __syncthreads();

@@ -196,6 +196,9 @@ def test_tiny_config_full_path(gpu_device):
     ("llama31_8b", 8, 8000, {"d": 7, "g": 50}),                # tree-configuration sweep of App. E:
     ("llama31_8b", 8, 8000, {"d": 8, "g": 70}),                # depth {6, 7, 8} x budget {50, 60, 70}
     ("llama31_8b", 8, 8000, {"d": 7, "g": 60}),                # the paper's own setting (App. B.1)
+    ("tiny", 96, 300, {"m": 96}),                              # one advantage group over the batch (wave per group)
+    ("tiny", 80, 300, {"m": 40}),                              # groups larger than 16, smaller than a wave
+    ("tiny", 48, 300, {"m": 16}),                              # largest group still summed by one thread
 ])
 def test_mid_size_full_path(gpu_device, name, R, V, kw):
     kw = dict(kw)

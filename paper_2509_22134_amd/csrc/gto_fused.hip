@@ -316,30 +316,39 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
           }
         } else
         if (ncols > 0) {
-          float cm = neg_inf();
-          for (int c2 = 0; c2 < ncols; ++c2) cm = fmaxf(cm, mine[c2]);
-          const float m_new = fmaxf(st.m, cm);
-          const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
-          const float scale = __builtin_amdgcn_exp2f(st.c - c_new);
-          double s = (st.m == neg_inf()) ? 0.0 : st.s * (double)scale;
-          float p = 0.f;
-          const float thr_v = st.v[KT - 1];
-          bool any_hit = false;
+          // One pass over the 64 new logits: maximum, sum of exp2 against the reference exponent the
+          // row already has (st.c, not necessarily its maximum), and the top-k insertions.  The sum is
+          // re-referenced only when the maximum has moved far above st.c, and recomputed in the rare
+          // case that the old reference could have overflowed (or when the row has none yet).
+          const bool have_ref = (st.m != neg_inf());
+          const float c_ref = have_ref ? st.c : 0.f;
+          float cm = neg_inf(), p = 0.f;
           for (int c2 = 0; c2 < ncols; ++c2) {
             const float x = mine[c2];
-            p += __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, -c_new));
-            any_hit = any_hit || (x > thr_v) || (st.id[KT - 1] == kNoId);
-          }
-          st.s = s + (double)p;
-          st.m = m_new;
-          st.c = c_new;
-          if (any_hit) {
-            for (int c2 = 0; c2 < ncols; ++c2) {
-              const float x = mine[c2];
+            cm = fmaxf(cm, x);
+            p += __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, -c_ref));
+            if (x >= st.v[KT - 1]) {
               const int xi = cbase + c2;
               if (better(x, xi, st.v[KT - 1], st.id[KT - 1])) list_insert<KT>(st.v, st.id, x, xi);
             }
           }
+          const float m_new = fmaxf(st.m, cm);
+          const float over = __builtin_fmaf(cm, kLog2e, -c_ref);     // how far the new maximum is above the reference
+          if (!have_ref || over > 100.f) {
+            const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
+            float p2 = 0.f;
+            for (int c2 = 0; c2 < ncols; ++c2) p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(mine[c2], kLog2e, -c_new));
+            const double s = have_ref ? st.s * (double)__builtin_amdgcn_exp2f(st.c - c_new) : 0.0;
+            st.s = s + (double)p2;
+            st.c = c_new;
+          } else if (over > 24.f) {
+            const float c_new = m_new * kLog2e;
+            st.s = (st.s + (double)p) * (double)__builtin_amdgcn_exp2f(st.c - c_new);
+            st.c = c_new;
+          } else {
+            st.s += (double)p;
+          }
+          st.m = m_new;
         }
       }
       __syncthreads();

@@ -137,6 +137,43 @@ def test_fused_sampled_walk(gpu_device):
     _compare_ppo(w, L, path)
 
 
+@pytest.mark.parametrize("nc", [1, 4])
+def test_fused_row_statistics_when_the_maximum_moves_far(gpu_device, nc):
+    """Logits that climb by tens and by hundreds along the vocabulary (and fall, for negative hidden
+    states): the running sum of a row has to be re-referenced, or recomputed, when a new tile's
+    maximum is far above the exponent reference the row carries.  All products and sums are exact in
+    fp32 here (hidden states and head rows are constant vectors of bf16 values), so ids are compared
+    exactly, ties included."""
+    _say(f"fused row statistics with a moving maximum, chunks={nc}")
+    R, d, k, hidden, V = 6, 2, 4, 64, 4096
+    v = torch.arange(V, dtype=torch.float32)
+    b = (v * (4.0 / V)).to(torch.bfloat16).float()        # slow climb: duplicates after rounding = ties
+    b = b + (v >= 1024).float() * 1.0 + (v >= 2560).float() * 2.5     # jumps of 64 and 160 in the logits
+    W = b[:, None].expand(V, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
+    scale = torch.tensor([1.0, -1.0, 0.5, -0.5, 2.0, 0.25])
+    H = scale[:, None, None, None].expand(R, d, k, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
+    cfg = G.make_config(R=R, d=d, k=k, g=4, V=V, dtype=torch.bfloat16)
+    ws = torch.empty(G.gto_fused_workspace_bytes(cfg, hidden), dtype=torch.uint8, device=gpu_device)
+    ds, ts = G.alloc_draft_stats(cfg, gpu_device), G.alloc_target_stats(cfg, gpu_device)
+    try:
+        G.gto_set_fused_tuning(nc, True)
+        G.gto_fused_draft_row_stats(cfg, H, W, ds, ws)
+        G.gto_fused_target_row_stats(cfg, H, W, ts, ws)
+        torch.cuda.synchronize()
+    finally:
+        G.gto_set_fused_tuning(0, True)
+    L = O.fused_logits(H.float().cpu().numpy(), W.float().cpu().numpy())
+    od, ot = O.draft_row_stats(L, k), O.target_row_stats(L)
+    gd, gt = U.to_np(ds), U.to_np(ts)
+    m = U.used_mask(R, d, k)
+    assert np.array_equal(gd["top_tok"][m], od["top_tok"][m])
+    assert np.array_equal(gt["t_argmax"][m], ot["t_argmax"][m])
+    assert np.array_equal(gd["row_max"][m], od["row_max"][m].astype(np.float32))
+    np.testing.assert_allclose(gd["row_lse"][m], od["row_lse"][m], rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(gt["t_lse"][m], ot["t_lse"][m], rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(gd["top_logp"][m], od["top_logp64"][m], rtol=1e-5, atol=4e-5)
+
+
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     _say("fused: chunk count / workgroup layout invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,

@@ -621,6 +621,28 @@ def ppo_surrogate_bwd(path, tree, fwd, D_cur, d_lse, adv, m: int, grad_scale: fl
     return dict(grad_rows=grad_rows, grad_slot=grad_slot, coef=coef)
 
 
+def ppo_surrogate_bwd_dh(bwd, W_vh: np.ndarray):
+    """Fused LM-head variant: gradient of grad_scale * loss w.r.t. the current draft model's hidden
+    states.  The logits of a slot are hidden . W^T, so by the chain rule the hidden state of the
+    slot behind step t of root i receives
+        dH[i, t, :] = sum_v G[i, t, v] W[v, :] = c_i (W[token_t, :] - sum_v p_v W[v, :]),
+    with G, c_i and p of ppo_surrogate_bwd (`bwd` is its result).  Returns dh_rows [R, d, hidden]
+    fp64 (zero where grad_slot is -1 or c_i = 0) and abs_bound [R, d, hidden] = sum_v |G| |W|, the
+    scale against which a lower-precision contraction is judged."""
+    G = bwd["grad_rows"]
+    W64 = np.asarray(W_vh, dtype=np.float64)
+    R, d, V = G.shape
+    dh = np.zeros((R, d, W64.shape[1]))
+    bound = np.zeros_like(dh)
+    absW = np.abs(W64)
+    for r in range(R):
+        for t in range(d):
+            if bwd["grad_slot"][r, t] >= 0 and bwd["coef"][r] != 0.0:
+                dh[r, t] = G[r, t] @ W64
+                bound[r, t] = np.abs(G[r, t]) @ absW
+    return dict(dh_rows=dh, abs_bound=bound)
+
+
 # --------------------------------------------------------------------- token-level loss
 def token_loss(D: np.ndarray, T: np.ndarray, weight=None, grad_scale: float = 1.0):
     """Token-level loss of Eq. 13 / App. B.2: mean over the supervised positions of the cross-entropy

@@ -193,3 +193,49 @@ def test_token_loss_matches_scipy_entropy_kl_and_finite_differences():
     Dq = D.copy(); Dq[:, 1] += 3.0
     assert O.token_loss(Dq, T)["loss"] == out["loss"]
     assert np.abs(ref["grad"].sum(axis=-1)).max() < 1e-15
+
+
+def test_bwd_dh_matches_central_finite_differences_through_the_lm_head():
+    """The hidden-state gradient of the fused variant against finite differences of the surrogate
+    taken through logits = hidden . W^T (tree, path and advantage held fixed, as in the method)."""
+    rng = np.random.default_rng(11)
+    R, d, k, V, Hd, g, m = 4, 3, 2, 9, 5, 8, 2
+    W = rng.normal(0, 0.7, size=(V, Hd))
+    H = rng.normal(0, 1.0, size=(R, d, k, Hd))
+    Href = H + rng.normal(0, 0.05, size=H.shape)
+    D, Dref = O.fused_logits(H, W), O.fused_logits(Href, W)
+    st, sr = O.draft_row_stats(D, k), O.draft_row_stats(Dref, k)
+    pool = O.expand_tree(st["top_tok"], st["top_logp32"], d, k)
+    tree = O.select_topg(pool, g)
+    T = rng.normal(0, 1.0, size=D.shape)
+    for r in range(R):
+        for (l, j) in O.used_slots(d, k):
+            T[r, l, j, st["top_tok"][r, l, j, 0]] = T[r, l, j].max() + 1.0
+    path = O.accepted_path(tree, O.target_row_stats(T)["t_argmax"], d)
+    adv = rng.normal(0, 1, R)
+    f = O.ppo_surrogate_fwd(path, tree, D, st["row_lse"], Dref, sr["row_lse"], adv, m, 0.2)
+    assert f["active"].sum() >= 2 and path["path_len"].max() >= 2
+    gs = 0.5
+    b = O.ppo_surrogate_bwd(path, tree, f, D, st["row_lse"], adv, m, gs)
+    got = O.ppo_surrogate_bwd_dh(b, W)
+
+    def loss_of(Hp):
+        Dp = O.fused_logits(Hp, W)
+        return _loss_of(Dp, tree, path, Dref, sr, adv, m, k)
+
+    h = 1e-5
+    full = np.zeros_like(H)
+    for idx in np.ndindex(*H.shape):
+        Hp, Hm = H.copy(), H.copy()
+        Hp[idx] += h
+        Hm[idx] -= h
+        full[idx] = gs * (loss_of(Hp) - loss_of(Hm)) / (2 * h)
+    mine = np.zeros_like(H)
+    for r in range(R):
+        for t in range(d):
+            j = b["grad_slot"][r, t]
+            if j >= 0:
+                mine[r, t, j] = got["dh_rows"][r, t]
+    np.testing.assert_allclose(mine, full, atol=3e-9)
+    assert np.abs(mine).max() > 1e-3
+    assert (got["abs_bound"] >= np.abs(got["dh_rows"]) - 1e-15).all()

@@ -283,6 +283,25 @@ int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
                                 const void *w_draft_vh, const gto_draft_stats *draft_stats_cur, float *grad_rows,
                                 int32_t *grad_slot, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same backward, carried on to the hidden states (the chain rule through logits = hidden . W^T;
+ * Eq. 11-12 for the surrogate): dh_rows[r, t, :] = sum_v G[r, t, v] w_draft[v, :] with G the gradient
+ * row gto_ppo_surrogate_bwd_fused would write, for the slot grad_slot[r, t] of level t.  The fp32
+ * gradient rows are not written; -coef * softmax of each path row is staged in the workspace as two
+ * bf16 planes (value = hi + lo, relative error <= 2^-16 per entry), contracted with the head on the
+ * matrix cores in fp32; the accepted token's own term coef * (1 - p_token) * w_draft[token, :] is added
+ * afterwards with 1 - p_token formed as the sum of the other probabilities (no cancellation).
+ *   w_draft_hv : the same head, hidden-major: bf16 [hidden_dim, V] (w_draft_hv[h, v] = w_draft_vh[v, h]);
+ *                the caller keeps this second copy so that both operands are contiguous along the vocabulary
+ *   dh_rows    : out, fp32 [R, d, hidden_dim]; rows with grad_slot = -1 or a zero coefficient are left
+ *                untouched (zeroed with GTO_FLAG_GRAD_ZERO_FILL)
+ * Requires V % 32 == 0 (GTO_E_SHAPE otherwise) and a workspace of gto_fused_dh_workspace_bytes. */
+int gto_fused_dh_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out);
+int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                   const gto_ppo *fwd, const void *hidden_cur, int32_t hidden_dim,
+                                   const void *w_draft_vh, const void *w_draft_hv,
+                                   const gto_draft_stats *draft_stats_cur, float *dh_rows, int32_t *grad_slot,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Tuning knob of the fused kernels: vocabulary chunks per row block (0 = per-launch choice) and
  * whether workgroups are laid out in per-XCD patches (default 1).  Process-wide. */
 int gto_set_fused_tuning(int n_chunks, int xcd_patches);

@@ -104,6 +104,9 @@ def lib():
                                               P(gto_draft_stats), VP, VP, VP, SZ, VP]
     L.gto_ppo_surrogate_fwd_fused.argtypes = [cfgp, P(gto_tree), P(gto_reward), VP, VP, C.c_int32, VP,
                                               P(gto_draft_stats), P(gto_draft_stats), VP, P(gto_ppo), VP, SZ, VP]
+    L.gto_fused_dh_workspace_bytes.argtypes = [cfgp, C.c_int32, P(C.c_size_t)]
+    L.gto_ppo_surrogate_bwd_fused_dh.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, C.c_int32, VP, VP,
+                                                 P(gto_draft_stats), VP, VP, VP, SZ, VP]
     L.gto_set_waves_per_row.argtypes = [C.c_int]
     L.gto_profile_enable.argtypes = [C.c_int]
     L.gto_profile_read.argtypes = [P(C.c_char_p), P(C.c_int32), P(C.c_double), C.c_int]
@@ -113,7 +116,8 @@ def lib():
                  "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
                  "gto_set_fused_tuning", "gto_expand_tree_fused", "gto_tree_reward_fused",
-                 "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused"):
+                 "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused",
+                 "gto_fused_dh_workspace_bytes", "gto_ppo_surrogate_bwd_fused_dh"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -358,6 +362,24 @@ def gto_ppo_surrogate_bwd_fused(cfg, tree_cur, path_cur, fwd, hidden_cur, w_draf
                                              hidden_cur.shape[-1], _dp(w_draft_vh), _ref(ds), _dp(grad_rows),
                                              _dp(grad_slot), ws, wb, _stream(stream)), "gto_ppo_surrogate_bwd_fused")
     return grad_rows, grad_slot
+
+
+def gto_fused_dh_workspace_bytes(cfg, hidden_dim: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().gto_fused_dh_workspace_bytes(C.byref(cfg), hidden_dim, C.byref(out)), "gto_fused_dh_workspace_bytes")
+    return out.value
+
+
+def gto_ppo_surrogate_bwd_fused_dh(cfg, tree_cur, path_cur, fwd, hidden_cur, w_draft_vh, w_draft_hv, draft_stats_cur,
+                                   dh_rows, grad_slot, workspace, stream=None):
+    t, w = _pack(gto_tree, _TREE, tree_cur), _pack(gto_reward, _REWARD, path_cur)
+    f, ds = _pack(gto_ppo, _PPO, fwd), _pack(gto_draft_stats, _DRAFT, draft_stats_cur)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_ppo_surrogate_bwd_fused_dh(C.byref(cfg), _ref(t), _ref(w), _ref(f), _dp(hidden_cur),
+                                                hidden_cur.shape[-1], _dp(w_draft_vh), _dp(w_draft_hv), _ref(ds),
+                                                _dp(dh_rows), _dp(grad_slot), ws, wb, _stream(stream)),
+           "gto_ppo_surrogate_bwd_fused_dh")
+    return dh_rows, grad_slot
 
 
 def gto_set_fused_tuning(n_chunks: int = 0, xcd_patches: bool = True) -> None:

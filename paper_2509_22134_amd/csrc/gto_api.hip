@@ -675,6 +675,104 @@ int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
   return hip_status();
 }
 
+// workspace of the hidden-state backward: the forward-style partial area is not needed; row lists and
+// count, the two bf16 planes [R d, V], the split partials [splits, R d, hidden]
+struct DhWs {
+  int n_splits, slabs_per_split, m_blocks, h_blocks;
+  size_t off_list_p, off_list_slot, off_count, off_s, off_hi, off_lo, off_partial, bytes;
+};
+DhWs dh_ws(const gto_config *c, int hidden_dim) {
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  DhWs L{};
+  const size_t rd = (size_t)c->R * c->d;
+  const int slabs = 2 * (c->V / 32);
+  const int want = 8;                               // splits of the contraction, so that few rows still fill the chip
+  L.slabs_per_split = (slabs + want - 1) / want;
+  L.n_splits = (slabs + L.slabs_per_split - 1) / L.slabs_per_split;
+  L.m_blocks = (int)((rd + 255) / 256);
+  L.h_blocks = (hidden_dim + 255) / 256;
+  size_t off = 0;
+  L.off_list_p = off; off += up(rd * sizeof(int32_t));
+  L.off_list_slot = off; off += up(rd * sizeof(int32_t));
+  L.off_count = off; off += 256;
+  L.off_s = off; off += up(rd * 64 * sizeof(double));     // at most 64 vocabulary chunks per row
+  L.off_hi = off; off += up(rd * (size_t)c->V * sizeof(uint16_t));
+  L.off_lo = off; off += up(rd * (size_t)c->V * sizeof(uint16_t));
+  L.off_partial = off; off += up((size_t)L.n_splits * rd * hidden_dim * sizeof(float));
+  L.bytes = off;
+  return L;
+}
+
+int gto_fused_dh_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out) {
+  if (!cfg || !bytes_out) return GTO_E_NULL;
+  GTO_TRY(check_cfg(cfg, true));
+  if (cfg->k > kFusedMaxK || hidden_dim < 64 || hidden_dim % 64 != 0 || cfg->V % 32 != 0) return GTO_E_SHAPE;
+  *bytes_out = dh_ws(cfg, hidden_dim).bytes;
+  return GTO_OK;
+}
+
+int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                   const gto_ppo *fwd, const void *hidden_cur, int32_t hidden_dim,
+                                   const void *w_draft_vh, const void *w_draft_hv,
+                                   const gto_draft_stats *draft_stats_cur, float *dh_rows, int32_t *grad_slot,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, true));
+  GTO_TRY(check_fused(cfg, hidden_cur, hidden_dim, w_draft_vh));
+  GTO_TRY(check_logits(w_draft_hv));
+  if (cfg->V % 32 != 0) return GTO_E_SHAPE;
+  GTO_TRY(check_tree(tree_cur));
+  GTO_TRY(check_reward(path_cur));
+  GTO_TRY(check_ppo(fwd));
+  if (!draft_stats_cur || !draft_stats_cur->row_lse || !dh_rows || !grad_slot) return GTO_E_NULL;
+  const DhWs L = dh_ws(cfg, hidden_dim);
+  GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int64_t rd = (int64_t)cfg->R * cfg->d;
+  char *base = static_cast<char *>(workspace);
+  int32_t *list_p = reinterpret_cast<int32_t *>(base + L.off_list_p);
+  int32_t *list_slot = reinterpret_cast<int32_t *>(base + L.off_list_slot);
+  int32_t *count = reinterpret_cast<int32_t *>(base + L.off_count);
+  uint16_t *hi = reinterpret_cast<uint16_t *>(base + L.off_hi);
+  uint16_t *lo = reinterpret_cast<uint16_t *>(base + L.off_lo);
+  {
+    gto::BwdRowsArgs b{};
+    b.R = cfg->R; b.d = cfg->d; b.k = cfg->k;
+    b.path_slot = path_cur->path_slot; b.coef = fwd->coef;
+    b.grad_slot = grad_slot; b.list_p = list_p; b.list_slot = list_slot; b.count = count;
+    ProfScope ps("bwd_rows", st);
+    gto::launch_bwd_rows(b, st);
+    if (cfg->flags & GTO_FLAG_GRAD_ZERO_FILL) gto::launch_zero_rows(dh_rows, grad_slot, (int)rd, hidden_dim, st);
+  }
+  {
+    // -coef * softmax of every path row, as two bf16 planes
+    const FusedPlan p = fused_plan(rd, cfg->V, 1);
+    gto::FusedArgs a{};
+    a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
+    a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
+    a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
+    a.xcd_patches = g_fused_patches;
+    a.list_p = list_p; a.coef = fwd->coef; a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g;
+    a.plane_hi = hi; a.plane_lo = lo; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node;
+    a.part_s = reinterpret_cast<double *>(base + L.off_s);
+    ProfScope ps("fused_rows_bwd_planes", st);
+    gto::launch_fused_rows(a, st);
+  }
+  {
+    gto::FusedDhArgs a{};
+    a.plane_hi = hi; a.plane_lo = lo; a.w_hv = w_draft_hv; a.w_vh = w_draft_vh;
+    a.hidden_dim = hidden_dim; a.V = cfg->V; a.d = cfg->d; a.g = cfg->g; a.M = rd; a.m_dev = count;
+    a.m_blocks = L.m_blocks; a.h_blocks = L.h_blocks; a.n_splits = L.n_splits; a.slabs_per_split = L.slabs_per_split;
+    a.partial = reinterpret_cast<float *>(base + L.off_partial);
+    a.part_s = reinterpret_cast<const double *>(base + L.off_s);
+    a.n_chunks = fused_plan(rd, cfg->V, 1).n_chunks;
+    a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
+    a.dh_rows = dh_rows;
+    ProfScope ps("fused_dh", st);
+    gto::launch_fused_dh(a, st);
+  }
+  return hip_status();
+}
+
 int gto_set_fused_tuning(int n_chunks, int xcd_patches) {
   g_fused_chunks = n_chunks > 0 ? n_chunks : 0;
   g_fused_patches = xcd_patches ? 1 : 0;

@@ -84,7 +84,102 @@ __device__ __forceinline__ void list_insert(float (&v)[KT], int (&id)[KT], float
   }
 }
 
-enum FusedMode { kFusedStats = 0, kFusedBwd = 1 };
+// acc += A . B^T over kt_count k slabs of 32, for the 256 x 256 tile of the workgroup; wave (wm, wn)
+// owns the 128 x 128 quadrant.  pa(s, j) / pb(s, j) give this lane's global address for load j
+// (16-row group 64 wave + 16 j) of slab s of the row operand / the column operand: the 16 bytes of
+// row ld_row + 16 j at k unit ld_unit of that slab (see the callers).  Every wave of the workgroup
+// calls this with the same kt_count; on return all fragment reads of the caller's wave are done.
+template <class PA, class PB>
+__device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds, unsigned wbase, int lane, int wm,
+                                              int wn, int kt_count, PA pa, PB pb) {
+  // k slab s lands in stage s % FNST; every wave issues 4 loads per operand and slab (load j = one
+  // 16-row group)
+  auto issue_a = [&](int s_, int j) {
+    load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024, pa(s_, j));
+  };
+  auto issue_b = [&](int s_, int j) {
+    load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + FBM * FROWB + j * 1024, pb(s_, j));
+  };
+  __syncthreads();                           // previous tile's epilogue no longer reads the staging area
+  // prologue: slabs 0 and 1 and the hidden-state half of slab 2 (its W half follows in the loop)
+#pragma unroll
+  for (int s_ = 0; s_ < 2; ++s_)
+    if (s_ < kt_count) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) issue_a(s_, j);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) issue_b(s_, j);
+    }
+  if (2 < kt_count) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) issue_a(2, j);
+    wait_vmcnt<12>();                        // slab 0 landed; slab 1 and half of slab 2 in flight
+  } else {
+    wait_vmcnt<0>();
+  }
+  __syncthreads();
+
+  // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
+  // 16-byte unit 2 h + (lane >> 5) of k half h sits at unit ^ ((row / 4) % 4).
+  const int fsw = ((lane >> 5) ^ ((lane >> 2) & 3)) * 16;
+  const int fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
+  const int fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
+  const unsigned char *ldsb = reinterpret_cast<const unsigned char *>(lds);
+  bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    fa[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fa_base + t * 32 * FROWB);
+    fb[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fb_base + t * 32 * FROWB);
+  }
+  // One k slab: 16 MFMAs per half, as four rows of four.  Between the rows sit one load and two
+  // fragment reads, so that the matrix pipe does not wait for their issue and the 32 loads a
+  // workgroup issues per slab reach the texture path evenly spread:
+  //   first half  : W loads of slab kt+2, fragments of the second half of slab kt
+  //   between     : wait until slab kt+1 has landed, barrier
+  //   second half : hidden-state loads of slab kt+3, first fragments of slab kt+1
+  for (int kt = 0; kt < kt_count; ++kt) {
+    const unsigned char *sS = ldsb + (kt % FNST) * FSTAGE_B;
+    const bool has_next = kt + 1 < kt_count;
+    const bool load_b = kt + 2 < kt_count;
+    const bool load_a = kt + 3 < kt_count;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // stage (kt+2) % 4 was last read as slab kt-2: every wave passed the barrier of slab kt-1 after that
+      if (load_b) issue_b(kt + 2, i);
+      fa[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fa_base ^ 32) + i * 32 * FROWB);
+      fb[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fb_base ^ 32) + i * 32 * FROWB);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (has_next) {
+      // this wave's share of slab kt+1 has landed when at most the 8 loads of slab kt+2 are still
+      // out; the barrier extends that to the other waves' shares, and tells that every wave is
+      // past its reads of slab kt-1, whose stage the next loads overwrite
+      if (load_b) wait_vmcnt<8>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+    }
+    const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (load_a) issue_a(kt + 3, i);
+      if (has_next) {
+        fa[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + i * 32 * FROWB);
+        fb[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + i * 32 * FROWB);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+enum FusedMode { kFusedStats = 0, kFusedBwd = 1, kFusedPlanes = 2 };
 
 template <int KT, int MODE>
 __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
@@ -150,7 +245,8 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   int b_tok = -1;
   float *b_out = nullptr;
   double b_others = 0.0;
-  if (MODE == kFusedBwd) {
+  uint16_t *p_hi = nullptr, *p_lo = nullptr;
+  if (MODE == kFusedBwd || MODE == kFusedPlanes) {
     const int64_t gme = row0 + tid;
     if (gme < M) {
       const int pidx = a.list_p[gme];
@@ -158,7 +254,12 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
       b_lse = a.lse_by_slot[a.row_list[gme]];
       b_coef = a.coef[rr];
       b_tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
-      b_out = a.grad_rows + (int64_t)pidx * a.V;
+      if (MODE == kFusedBwd) {
+        b_out = a.grad_rows + (int64_t)pidx * a.V;
+      } else {
+        p_hi = a.plane_hi + gme * a.V;
+        p_lo = a.plane_lo + gme * a.V;
+      }
     }
   }
 
@@ -179,91 +280,9 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // k slab s lands in stage s % FNST; every wave issues 4 loads per operand and slab (load j = one
-    // 16-row group)
-    auto issue_a = [&](int s_, int j) {
-      load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024, a_ptr[j] + s_ * FBK);
-    };
-    auto issue_b = [&](int s_, int j) {
-      load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + FBM * FROWB + j * 1024, b_ptr[j] + s_ * FBK);
-    };
-    __syncthreads();                           // previous tile's epilogue no longer reads the staging area
-    // prologue: slabs 0 and 1 and the hidden-state half of slab 2 (its W half follows in the loop)
-#pragma unroll
-    for (int s_ = 0; s_ < 2; ++s_)
-      if (s_ < kt_count) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) issue_a(s_, j);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) issue_b(s_, j);
-      }
-    if (2 < kt_count) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) issue_a(2, j);
-      wait_vmcnt<12>();                        // slab 0 landed; slab 1 and half of slab 2 in flight
-    } else {
-      wait_vmcnt<0>();
-    }
-    __syncthreads();
-
-    // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
-    // 16-byte unit 2 h + (lane >> 5) of k half h sits at unit ^ ((row / 4) % 4).
-    const int fsw = ((lane >> 5) ^ ((lane >> 2) & 3)) * 16;
-    const int fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
-    const int fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
-    const unsigned char *ldsb = reinterpret_cast<const unsigned char *>(lds);
-    bf16x8 fa[2][4], fb[2][4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      fa[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fa_base + t * 32 * FROWB);
-      fb[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fb_base + t * 32 * FROWB);
-    }
-    // One k slab: 16 MFMAs per half, as four rows of four.  Between the rows sit one load and two
-    // fragment reads, so that the matrix pipe does not wait for their issue and the 32 loads a
-    // workgroup issues per slab reach the texture path evenly spread:
-    //   first half  : W loads of slab kt+2, fragments of the second half of slab kt
-    //   between     : wait until slab kt+1 has landed, barrier
-    //   second half : hidden-state loads of slab kt+3, first fragments of slab kt+1
-    for (int kt = 0; kt < kt_count; ++kt) {
-      const unsigned char *sS = ldsb + (kt % FNST) * FSTAGE_B;
-      const bool has_next = kt + 1 < kt_count;
-      const bool load_b = kt + 2 < kt_count;
-      const bool load_a = kt + 3 < kt_count;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        // stage (kt+2) % 4 was last read as slab kt-2: every wave passed the barrier of slab kt-1 after that
-        if (load_b) issue_b(kt + 2, i);
-        fa[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fa_base ^ 32) + i * 32 * FROWB);
-        fb[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fb_base ^ 32) + i * 32 * FROWB);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (has_next) {
-        // this wave's share of slab kt+1 has landed when at most the 8 loads of slab kt+2 are still
-        // out; the barrier extends that to the other waves' shares, and tells that every wave is
-        // past its reads of slab kt-1, whose stage the next loads overwrite
-        if (load_b) wait_vmcnt<8>();
-        else wait_vmcnt<0>();
-        __syncthreads();
-      }
-      const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (load_a) issue_a(kt + 3, i);
-        if (has_next) {
-          fa[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + i * 32 * FROWB);
-          fb[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + i * 32 * FROWB);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+    tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count,
+                  [&](int s_, int j) { return a_ptr[j] + s_ * FBK; },
+                  [&](int s_, int j) { return b_ptr[j] + s_ * FBK; });
     __syncthreads();                           // all fragment reads done before the staging area is written
 
     // ---- epilogue: four 64-column quarters through the staging area; thread t owns row t
@@ -289,6 +308,37 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
         const float *mine = stg + tid * FSTG_LD;
         const int cbase = n0 + qd * 64;
         const int ncols = min(64, a.V - cbase);     // <= 0 for quarters beyond the vocabulary
+        if (MODE == kFusedPlanes) {
+          // -coef * softmax as hi + lo in bf16 (V is a multiple of 32 in this mode: whole 16-byte stores);
+          // the accepted token's entry is left out (zero) and the other probabilities are summed, so that
+          // its coefficient coef * (1 - p_token) can be formed without cancellation afterwards
+          if (ncols > 0 && p_hi != nullptr) {
+            float part = 0.f;
+            for (int c8 = 0; c8 < ncols; c8 += 8) {
+              uint16_t hq[8], lq[8];
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const bool is_tok = (cbase + c8 + e == b_tok);
+                const float pv = is_tok ? 0.f : __builtin_amdgcn_exp2f((mine[c8 + e] - b_lse) * kLog2e);
+                part += pv;
+                const float gv = -b_coef * pv;
+                const __bf16 hb = (__bf16)gv;
+                const __bf16 lb = (__bf16)(gv - (float)hb);
+                hq[e] = __builtin_bit_cast(uint16_t, hb);
+                lq[e] = __builtin_bit_cast(uint16_t, lb);
+              }
+              u32x4 ho, lo;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                ho[e] = (uint32_t)hq[2 * e] | ((uint32_t)hq[2 * e + 1] << 16);
+                lo[e] = (uint32_t)lq[2 * e] | ((uint32_t)lq[2 * e + 1] << 16);
+              }
+              *reinterpret_cast<u32x4 *>(p_hi + cbase + c8) = ho;
+              *reinterpret_cast<u32x4 *>(p_lo + cbase + c8) = lo;
+            }
+            b_others += (double)part;
+          }
+        } else
         if (MODE == kFusedBwd) {
           if (ncols > 0 && b_out != nullptr) {
             float part = 0.f;
@@ -357,7 +407,7 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 
   // ---- partial results of this (row, chunk)
   const int64_t g = row0 + tid;
-  if (MODE == kFusedBwd) {
+  if (MODE == kFusedBwd || MODE == kFusedPlanes) {
     if (g < M) a.part_s[g * a.n_chunks + chunk] = b_others;
     return;
   }
@@ -543,6 +593,89 @@ __global__ __launch_bounds__(64) void k_gather_dot(GatherDotArgs a) {
   if (lane == 0) a.out[p] = acc;
 }
 
+// Hidden-state gradient, one 256 (rows of the list) x 256 (hidden columns) tile per workgroup and split of
+// the contraction: partial[split] = sum over the split's k slabs of G . W, G = [plane_hi | plane_lo]
+// (contraction length 2 V), W hidden-major so that both operands are contiguous along the vocabulary.
+__global__ __launch_bounds__(256) void k_fused_dh(FusedDhArgs a) {
+  extern __shared__ __align__(16) uint16_t lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int split = blockIdx.x % a.n_splits;
+  const int rest = blockIdx.x / a.n_splits;
+  const int hblock = rest % a.h_blocks, mblock = rest / a.h_blocks;
+  const int64_t M = min((int64_t)*a.m_dev, a.M);
+  const int64_t row0 = (int64_t)mblock * FBM;
+  if (row0 >= M) return;
+  const int nks = a.V / FBK;                                  // slabs per plane
+  const int s0 = split * a.slabs_per_split;
+  const int kt_count = min(a.slabs_per_split, 2 * nks - s0);  // >= 1 by the launch geometry
+  const int h0 = hblock * FBN;
+  const int ld_row = 64 * wave + (lane >> 2);
+  const int ld_unit = (lane & 3) ^ ((lane >> 4) & 3);
+  const uint16_t *a_hi[4], *a_lo[4], *b_ptr[4];
+  const uint16_t *Wp = static_cast<const uint16_t *>(a.w_hv);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int64_t g = row0 + ld_row + 16 * j;
+    if (g >= M) g = M - 1;
+    a_hi[j] = a.plane_hi + g * a.V + ld_unit * 8;
+    a_lo[j] = a.plane_lo + g * a.V + ld_unit * 8;
+    int n = h0 + ld_row + 16 * j;
+    if (n >= a.hidden_dim) n = a.hidden_dim - 1;
+    b_ptr[j] = Wp + (int64_t)n * a.V + ld_unit * 8;
+  }
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)lds;
+  const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)wave * 4096u);
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count,
+                [&](int s_, int j) {
+                  const int sg = s0 + s_;
+                  return (sg < nks) ? a_hi[j] + sg * FBK : a_lo[j] + (sg - nks) * FBK;
+                },
+                [&](int s_, int j) {
+                  const int sg = s0 + s_;
+                  return b_ptr[j] + ((sg < nks) ? sg : sg - nks) * FBK;
+                });
+  float *out = a.partial + (int64_t)split * a.M * a.hidden_dim;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int64_t row = row0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const int col = h0 + wn * 128 + j * 32 + (lane & 31);
+        if (row < M && col < a.hidden_dim) out[row * a.hidden_dim + col] = acc[i][j][e];
+      }
+}
+
+// dH row of list entry g: the splits in a fixed order, plus the accepted token's own term
+// coef * (1 - p_token) * W[token, :], with 1 - p_token taken as the sum of the other probabilities.
+__global__ __launch_bounds__(256) void k_fused_dh_reduce(FusedDhArgs a) {
+  const int64_t g = blockIdx.x;
+  if (g >= (int64_t)*a.m_dev) return;
+  const int pidx = a.list_p[g];
+  const int rr = pidx / a.d;
+  const int tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+  const float coef = a.coef[rr];
+  const uint16_t *wrow = static_cast<const uint16_t *>(a.w_vh) + (int64_t)tok * a.hidden_dim;
+  double others = 0.0;                       // sum of the probabilities of all tokens but the accepted one
+  for (int c = 0; c < a.n_chunks; ++c) others += a.part_s[g * a.n_chunks + c];
+  const float ctok = (float)((double)coef * others);
+  for (int h = threadIdx.x; h < a.hidden_dim; h += 256) {
+    float sum = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) sum += a.partial[((int64_t)s * a.M + g) * a.hidden_dim + h];
+    a.dh_rows[(int64_t)pidx * a.hidden_dim + h] = __builtin_fmaf(ctok, Elem<uint16_t>::load1(wrow + h), sum);
+  }
+}
+
 template <typename K>
 static void set_lds_attr(K kern) {
   (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -555,17 +688,25 @@ static int fused_grid(const FusedArgs &a) {
   return ((pms * pcs + 7) / 8) * 8 * 32;
 }
 
-void launch_fused_rows(const FusedArgs &a, hipStream_t st) {
+static void ensure_lds_attrs() {
   static bool attr_set = false;
   if (!attr_set) {
     set_lds_attr(k_fused_rows<1, kFusedStats>);
     set_lds_attr(k_fused_rows<8, kFusedStats>);
     set_lds_attr(k_fused_rows<16, kFusedStats>);
     set_lds_attr(k_fused_rows<1, kFusedBwd>);
+    set_lds_attr(k_fused_rows<1, kFusedPlanes>);
+    set_lds_attr(k_fused_dh);
     attr_set = true;
   }
+}
+
+void launch_fused_rows(const FusedArgs &a, hipStream_t st) {
+  ensure_lds_attrs();
   const int blocks = fused_grid(a);
-  if (a.grad_rows != nullptr)
+  if (a.plane_hi != nullptr)
+    hipLaunchKernelGGL((k_fused_rows<1, kFusedPlanes>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+  else if (a.grad_rows != nullptr)
     hipLaunchKernelGGL((k_fused_rows<1, kFusedBwd>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
   else if (a.ktop <= 1)
     hipLaunchKernelGGL((k_fused_rows<1, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
@@ -573,6 +714,12 @@ void launch_fused_rows(const FusedArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((k_fused_rows<8, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
   else
     hipLaunchKernelGGL((k_fused_rows<16, kFusedStats>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+}
+
+void launch_fused_dh(const FusedDhArgs &a, hipStream_t st) {
+  ensure_lds_attrs();
+  hipLaunchKernelGGL(k_fused_dh, dim3((unsigned)(a.m_blocks * a.h_blocks * a.n_splits)), dim3(256), kFusedLdsBytes, st, a);
+  hipLaunchKernelGGL(k_fused_dh_reduce, dim3((unsigned)a.M), dim3(256), 0, st, a);
 }
 
 void launch_fused_bwd_fixup(const FusedArgs &a, hipStream_t st) {

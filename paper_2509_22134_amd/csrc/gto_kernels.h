@@ -103,6 +103,27 @@ struct FusedArgs {
   const float *coef, *lse_by_slot;
   int g;
   float *grad_rows;          // [R, d, V]
+  // plane mode (plane_hi != null, instead of grad_rows): -coef * softmax of row i of the list is split
+  // into two bf16 planes [M, V] (value = hi + lo; zero at the accepted token), the row operand of the
+  // hidden-state gradient; part_s receives the sum of the other probabilities as in the backward mode
+  uint16_t *plane_hi, *plane_lo;
+};
+
+// Hidden-state gradient dH = G . W of the fused variant: G = the two bf16 planes, W hidden-major.
+struct FusedDhArgs {
+  const uint16_t *plane_hi, *plane_lo;   // [M, V]
+  const void *w_hv;          // bf16 [hidden_dim, V]
+  const void *w_vh;          // bf16 [V, hidden_dim] (row of the accepted token, added exactly)
+  int hidden_dim, V, d, g;
+  int64_t M;                 // capacity of the row list
+  const int32_t *m_dev;      // actual row count
+  int m_blocks, h_blocks, n_splits, slabs_per_split;
+  float *partial;            // [n_splits, M, hidden_dim]
+  const double *part_s;      // [M, n_chunks] sum of the non-token probabilities per vocabulary chunk of the plane pass
+  int n_chunks;
+  const int32_t *list_p, *sel_tok, *path_node;
+  const float *coef;
+  float *dh_rows;            // [R, d, hidden_dim]
 };
 
 struct BwdRowsArgs {
@@ -131,6 +152,7 @@ struct PairArgs {
 void launch_pairs(const PairArgs &a, int mode, hipStream_t st);
 void launch_fused_rows(const FusedArgs &a, hipStream_t st);
 void launch_fused_bwd_fixup(const FusedArgs &a, hipStream_t st);
+void launch_fused_dh(const FusedDhArgs &a, hipStream_t st);
 void launch_bwd_rows(const BwdRowsArgs &a, hipStream_t st);
 void launch_zero_rows(float *grad_rows, const int32_t *grad_slot, int rows, int V, hipStream_t st);
 void launch_compact_flags(const int32_t *flags, int n, int32_t *list, int32_t *count, hipStream_t st);

@@ -71,7 +71,7 @@ class GtoFusedPath:
     (draft head for both draft models, target head for the target)."""
 
     def __init__(self, *, R, d, k, g, V, hidden, group_size, device, eta=1.0, eps=0.2, delta=1e-6,
-                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0):
+                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0, want_dh=False):
         self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=B.GTO_BF16, group_size=group_size,
                                  reward_mode=reward_mode, eta=eta, eps=eps, delta=delta, grad_scale=grad_scale,
                                  flags=flags, path_mode=path_mode)
@@ -88,6 +88,13 @@ class GtoFusedPath:
         if want_grad:
             self.grad_rows = torch.empty((R, d, V), dtype=torch.float32, device=device)
             self.grad_slot = torch.empty((R, d), dtype=torch.int32, device=device)
+        self.want_dh = want_dh
+        if want_dh:
+            # gradient w.r.t. the hidden states instead of (or next to) the logits rows
+            self.dh_rows = torch.empty((R, d, hidden), dtype=torch.float32, device=device)
+            self.dh_slot = torch.empty((R, d), dtype=torch.int32, device=device)
+            self.dh_workspace = torch.empty((B.gto_fused_dh_workspace_bytes(self.cfg, hidden),), dtype=torch.uint8,
+                                            device=device)
 
     def build_and_score(self, tag, H, W_draft, W_target):
         b = self.buf[tag]
@@ -95,7 +102,8 @@ class GtoFusedPath:
         B.gto_select_topg(self.cfg, b["pool"], b["tree"])
         B.gto_tree_reward_fused(self.cfg, b["tree"], H, W_target, b["tstats"], b["reward"], self.workspace)
 
-    def step(self, H_cur, H_ref, W_draft, W_target, accept_u=None):
+    def step(self, H_cur, H_ref, W_draft, W_target, accept_u=None, W_draft_hv=None):
+        """W_draft_hv: the draft head hidden-major ([hidden, V]), needed with want_dh only."""
         for tag in self.buf:
             if accept_u:
                 self.buf[tag]["reward"]["accept_u"] = accept_u[tag]
@@ -110,3 +118,6 @@ class GtoFusedPath:
         if self.want_grad:
             B.gto_ppo_surrogate_bwd_fused(self.cfg, cur["tree"], cur["reward"], self.ppo, H_cur, W_draft, cur["dstats"],
                                           self.grad_rows, self.grad_slot, self.workspace)
+        if self.want_dh:
+            B.gto_ppo_surrogate_bwd_fused_dh(self.cfg, cur["tree"], cur["reward"], self.ppo, H_cur, W_draft, W_draft_hv,
+                                             cur["dstats"], self.dh_rows, self.dh_slot, self.dh_workspace)

@@ -174,6 +174,55 @@ def test_fused_row_statistics_when_the_maximum_moves_far(gpu_device, nc):
     np.testing.assert_allclose(gd["top_logp"][m], od["top_logp64"][m], rtol=1e-5, atol=4e-5)
 
 
+@pytest.mark.parametrize("R,d,k,g,hidden,V,flags", [
+    (40, 3, 8, 20, 256, 3072, 0),                               # one row block of path rows
+    (200, 3, 4, 12, 320, 2048, 0),                              # several row blocks, ragged hidden tile (320 = 256 + 64)
+    (24, 4, 8, 24, 128, 4096, G.GTO_FLAG_GRAD_ZERO_FILL),
+])
+def test_fused_hidden_state_gradient(gpu_device, R, d, k, g, hidden, V, flags):
+    """dH = G . W of the fused backward against the oracle's fp64 contraction.  Tolerance: the gradient
+    row is staged as hi + lo bf16 (2^-17 relative per entry), built from fp32 logits (error E) and
+    summed in fp32, all relative to sum_v |G| |W| (the oracle's abs_bound)."""
+    w = S.FusedWorkload("case", R=R, V=V, k=k, d=d, g=g, m=8, hidden=hidden, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    _say(f"fused dH R={R} d={d} k={k} hidden={hidden} V={V} flags={flags}")
+    t = S.make_fused(w, gpu_device)
+    W_hv = t["W_draft"].t().contiguous()
+    path = GtoFusedPath(R=R, d=d, k=k, g=g, V=V, hidden=hidden, group_size=w.m, device=gpu_device, eta=w.eta,
+                        eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags, want_dh=True)
+    path.grad_rows.fill_(7.0)
+    path.dh_rows.fill_(7.0)
+    path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"], W_draft_hv=W_hv)
+    torch.cuda.synchronize()
+    L = _oracle_logits(t, list(range(R)))
+    E = logit_error_bound(hidden, max(float(np.abs(v).max()) for v in L.values()))
+    # the oracle's backward on the GPU's own tree, path, advantage and ratio (as in _compare_ppo)
+    cur = path.buf["cur"]
+    g_tree, g_rew = U.to_np(cur["tree"]), U.to_np(cur["reward"])
+    gpath = {n: g_rew[n] for n in U.INT_PATH}
+    gp = U.to_np(path.ppo)
+    g_adv = path.adv.cpu().numpy().astype(np.float64)
+    od = O.draft_row_stats(L["D_cur"], k)
+    f2 = dict(active=gp["active"], ratio=gp["ratio"].astype(np.float64))
+    b2 = O.ppo_surrogate_bwd(gpath, g_tree, f2, L["D_cur"], od["row_lse"], g_adv, w.m, 0.5)
+    want = O.ppo_surrogate_bwd_dh(b2, t["W_draft"].double().cpu().numpy())
+    got = path.dh_rows.cpu().numpy()
+    slot = path.dh_slot.cpu().numpy()
+    assert np.array_equal(slot, path.grad_slot.cpu().numpy())
+    live = (slot >= 0) & (b2["coef"] != 0)[:, None]
+    assert live.sum() >= 8, "the case must exercise some rows"
+    tol = (2.0 ** -17 + 2 * E + 1e-6) * want["abs_bound"] + 1e-30
+    err = np.abs(got - want["dh_rows"])
+    assert (err[live] <= tol[live]).all(), float((err[live] / tol[live]).max())
+    assert np.abs(want["dh_rows"][live]).max() > 0
+    dead = ~live
+    if flags & G.GTO_FLAG_GRAD_ZERO_FILL:
+        assert not got[slot < 0].any()
+    else:
+        assert (got[slot < 0] == 7.0).all()
+    _say(f"  rows with a gradient: {int(live.sum())}, worst error / tolerance {float((err[live] / tol[live]).max()):.3f}")
+
+
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     _say("fused: chunk count / workgroup layout invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,

@@ -302,6 +302,24 @@ int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_c
                                    const gto_draft_stats *draft_stats_cur, float *dh_rows, int32_t *grad_slot,
                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Token-level loss (Eq. 13, App. B.2) of the fused variant.  The root-row logits of the draft and the
+ * target head are produced on the matrix cores and kept in the workspace as fp32 [R, V] each (the
+ * root rows are 1 / rho of all rows; every other logit still never reaches HBM), then reduced by the
+ * kernels of gto_token_loss_fwd / _bwd.  draft_stats->row_lse and target_stats->t_lse must hold the
+ * root slots' log-sum-exps (gto_expand_tree_fused / gto_tree_reward_fused write them).  The backward
+ * reads the logits the forward left in `workspace`: same buffer, untouched in between.  Outputs and
+ * weight / inv_count / grad_scale semantics as in the streaming calls. */
+int gto_fused_token_loss_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out);
+int gto_token_loss_fwd_fused(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_draft_vh,
+                             const void *w_target_vh, const gto_draft_stats *draft_stats,
+                             const gto_target_stats *target_stats, const float *weight_or_null, float *loss_rows,
+                             float *loss, float *inv_count, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+int gto_token_loss_bwd_fused(const gto_config *cfg, const gto_draft_stats *draft_stats,
+                             const gto_target_stats *target_stats, const float *weight_or_null,
+                             const float *inv_count, float grad_scale, float *grad_rows0, const void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
 /* Tuning knob of the fused kernels: vocabulary chunks per row block (0 = per-launch choice) and
  * whether workgroups are laid out in per-XCD patches (default 1).  Process-wide. */
 int gto_set_fused_tuning(int n_chunks, int xcd_patches);

@@ -93,6 +93,11 @@ def lib():
     L.gto_calibration_copy.argtypes = [VP, VP, SZ, VP]
     L.gto_token_loss_fwd.argtypes = [cfgp, VP, VP, P(gto_draft_stats), P(gto_target_stats), VP, VP, VP, VP, VP]
     L.gto_token_loss_bwd.argtypes = [cfgp, VP, VP, P(gto_draft_stats), P(gto_target_stats), VP, VP, C.c_float, VP, VP]
+    L.gto_fused_token_loss_workspace_bytes.argtypes = [cfgp, C.c_int32, P(C.c_size_t)]
+    L.gto_token_loss_fwd_fused.argtypes = [cfgp, VP, C.c_int32, VP, VP, P(gto_draft_stats), P(gto_target_stats), VP, VP,
+                                           VP, VP, VP, SZ, VP]
+    L.gto_token_loss_bwd_fused.argtypes = [cfgp, P(gto_draft_stats), P(gto_target_stats), VP, VP, C.c_float, VP, VP, SZ,
+                                           VP]
     L.gto_fused_workspace_bytes.argtypes = [cfgp, C.c_int32, P(SZ)]
     L.gto_fused_draft_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), VP, VP, SZ, VP]
     L.gto_fused_target_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_target_stats), VP, SZ, VP]
@@ -117,7 +122,8 @@ def lib():
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
                  "gto_set_fused_tuning", "gto_expand_tree_fused", "gto_tree_reward_fused",
                  "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused",
-                 "gto_fused_dh_workspace_bytes", "gto_ppo_surrogate_bwd_fused_dh"):
+                 "gto_fused_dh_workspace_bytes", "gto_ppo_surrogate_bwd_fused_dh",
+                 "gto_fused_token_loss_workspace_bytes", "gto_token_loss_fwd_fused", "gto_token_loss_bwd_fused"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -401,6 +407,33 @@ def gto_token_loss_bwd(cfg, draft_logits, target_logits, draft_stats, target_sta
     _check(lib().gto_token_loss_bwd(C.byref(cfg), _dp(draft_logits), _dp(target_logits), _ref(ds), _ref(ts),
                                     _dp(weight), _dp(inv_count), float(grad_scale), _dp(grad_rows0), _stream(stream)),
            "gto_token_loss_bwd")
+    return grad_rows0
+
+
+def gto_fused_token_loss_workspace_bytes(cfg, hidden_dim: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().gto_fused_token_loss_workspace_bytes(C.byref(cfg), hidden_dim, C.byref(out)),
+           "gto_fused_token_loss_workspace_bytes")
+    return out.value
+
+
+def gto_token_loss_fwd_fused(cfg, hidden, w_draft_vh, w_target_vh, draft_stats, target_stats, weight, loss_rows, loss,
+                             inv_count, workspace, stream=None):
+    ds, ts = _pack(gto_draft_stats, _DRAFT, draft_stats), _pack(gto_target_stats, _TARGET, target_stats)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_token_loss_fwd_fused(C.byref(cfg), _dp(hidden), hidden.shape[-1], _dp(w_draft_vh), _dp(w_target_vh),
+                                          _ref(ds), _ref(ts), _dp(weight), _dp(loss_rows), _dp(loss), _dp(inv_count),
+                                          ws, wb, _stream(stream)), "gto_token_loss_fwd_fused")
+    return loss_rows, loss
+
+
+def gto_token_loss_bwd_fused(cfg, draft_stats, target_stats, weight, inv_count, grad_scale, grad_rows0, workspace,
+                             stream=None):
+    ds, ts = _pack(gto_draft_stats, _DRAFT, draft_stats), _pack(gto_target_stats, _TARGET, target_stats)
+    ws, wb = _ws(workspace)
+    _check(lib().gto_token_loss_bwd_fused(C.byref(cfg), _ref(ds), _ref(ts), _dp(weight), _dp(inv_count),
+                                          float(grad_scale), _dp(grad_rows0), ws, wb, _stream(stream)),
+           "gto_token_loss_bwd_fused")
     return grad_rows0
 
 

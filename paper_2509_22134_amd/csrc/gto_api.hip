@@ -822,6 +822,91 @@ int gto_token_loss_bwd(const gto_config *cfg, const void *draft_logits, const vo
   return hip_status();
 }
 
+// fused token loss: workspace = [draft root logits | target root logits], fp32 [R, pitch] each
+struct TokWs {
+  int64_t pitch;
+  size_t off_d, off_t, bytes;
+};
+TokWs tok_ws(const gto_config *c) {
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  TokWs L{};
+  L.pitch = ((int64_t)c->V + 3) & ~(int64_t)3;
+  L.off_d = 0;
+  L.off_t = up((size_t)c->R * L.pitch * sizeof(float));
+  L.bytes = L.off_t + up((size_t)c->R * L.pitch * sizeof(float));
+  return L;
+}
+
+int gto_fused_token_loss_workspace_bytes(const gto_config *cfg, int32_t hidden_dim, size_t *bytes_out) {
+  if (!cfg || !bytes_out) return GTO_E_NULL;
+  GTO_TRY(check_cfg(cfg, false));
+  if (cfg->k > kFusedMaxK || hidden_dim < 64 || hidden_dim % 64 != 0) return GTO_E_SHAPE;
+  *bytes_out = tok_ws(cfg).bytes;
+  return GTO_OK;
+}
+
+int gto_token_loss_fwd_fused(const gto_config *cfg, const void *hidden, int32_t hidden_dim, const void *w_draft_vh,
+                             const void *w_target_vh, const gto_draft_stats *draft_stats,
+                             const gto_target_stats *target_stats, const float *weight_or_null, float *loss_rows,
+                             float *loss, float *inv_count, void *workspace, size_t workspace_bytes,
+                             void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, false));
+  GTO_TRY(check_fused(cfg, hidden, hidden_dim, w_draft_vh));
+  GTO_TRY(check_logits(w_target_vh));
+  if (!draft_stats || !draft_stats->row_lse || !target_stats || !target_stats->t_lse || !loss_rows || !loss ||
+      !inv_count)
+    return GTO_E_NULL;
+  const TokWs L = tok_ws(cfg);
+  GTO_TRY(check_ws(workspace, workspace_bytes, L.bytes));
+  hipStream_t st = (hipStream_t)hip_stream;
+  char *base = static_cast<char *>(workspace);
+  float *dl = reinterpret_cast<float *>(base + L.off_d), *tl = reinterpret_cast<float *>(base + L.off_t);
+  for (int which = 0; which < 2; ++which) {
+    // root rows only: with one used row per root, row i of the pass is slot (0,0) of root i
+    const FusedPlan p = fused_plan(cfg->R, cfg->V, 1);
+    gto::FusedArgs a{};
+    a.hidden = hidden; a.w = which ? w_target_vh : w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = 1;
+    a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = cfg->R;
+    a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
+    a.xcd_patches = g_fused_patches;
+    a.store_rows = which ? tl : dl; a.store_pitch = L.pitch;
+    ProfScope ps(which ? "fused_root_logits_target" : "fused_root_logits_draft", st);
+    gto::launch_fused_rows(a, st);
+  }
+  gto::TokenLossArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.V = cfg->V; a.row_stride = L.pitch; a.root_stride = L.pitch;
+  a.draft_logits = dl; a.target_logits = tl;
+  a.d_lse = draft_stats->row_lse; a.t_lse = target_stats->t_lse; a.weight = weight_or_null;
+  a.loss_rows = loss_rows; a.loss = loss; a.inv_count_out = inv_count;
+  {
+    ProfScope ps("token_loss_fwd", st);
+    gto::launch_token_loss(a, GTO_F32, false, st);
+  }
+  return hip_status();
+}
+
+int gto_token_loss_bwd_fused(const gto_config *cfg, const gto_draft_stats *draft_stats,
+                             const gto_target_stats *target_stats, const float *weight_or_null,
+                             const float *inv_count, float grad_scale, float *grad_rows0, const void *workspace,
+                             size_t workspace_bytes, void *hip_stream) {
+  GTO_TRY(check_cfg(cfg, false));
+  if (!draft_stats || !draft_stats->row_lse || !target_stats || !target_stats->t_lse || !inv_count || !grad_rows0)
+    return GTO_E_NULL;
+  const TokWs L = tok_ws(cfg);
+  GTO_TRY(check_ws(const_cast<void *>(workspace), workspace_bytes, L.bytes));
+  const char *base = static_cast<const char *>(workspace);
+  gto::TokenLossArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.V = cfg->V; a.row_stride = L.pitch; a.root_stride = L.pitch;
+  a.draft_logits = base + L.off_d; a.target_logits = base + L.off_t;
+  a.d_lse = draft_stats->row_lse; a.t_lse = target_stats->t_lse; a.weight = weight_or_null;
+  a.grad_scale = grad_scale; a.inv_count = inv_count; a.grad = grad_rows0;
+  {
+    ProfScope ps("token_loss_bwd", (hipStream_t)hip_stream);
+    gto::launch_token_loss(a, GTO_F32, true, (hipStream_t)hip_stream);
+  }
+  return hip_status();
+}
+
 int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
   if (!src || !dst) return GTO_E_NULL;
   if (bytes == 0 || bytes % 16 != 0) return GTO_E_SHAPE;

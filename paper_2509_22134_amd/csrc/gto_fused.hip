@@ -179,7 +179,7 @@ __device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds
   }
 }
 
-enum FusedMode { kFusedStats = 0, kFusedBwd = 1, kFusedPlanes = 2 };
+enum FusedMode { kFusedStats = 0, kFusedBwd = 1, kFusedPlanes = 2, kFusedStore = 3 };
 
 template <int KT, int MODE>
 __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
@@ -308,6 +308,21 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
         const float *mine = stg + tid * FSTG_LD;
         const int cbase = n0 + qd * 64;
         const int ncols = min(64, a.V - cbase);     // <= 0 for quarters beyond the vocabulary
+        if (MODE == kFusedStore) {
+          const int64_t gme = row0 + tid;
+          if (ncols > 0 && gme < M) {
+            float *o = a.store_rows + gme * a.store_pitch + cbase;
+            if (ncols == 64) {
+#pragma unroll
+              for (int c4 = 0; c4 < 64; c4 += 4) {
+                const f32x4 q = {mine[c4], mine[c4 + 1], mine[c4 + 2], mine[c4 + 3]};
+                *reinterpret_cast<f32x4 *>(o + c4) = q;
+              }
+            } else {
+              for (int c2 = 0; c2 < ncols; ++c2) o[c2] = mine[c2];
+            }
+          }
+        } else
         if (MODE == kFusedPlanes) {
           // -coef * softmax as hi + lo in bf16 (V is a multiple of 32 in this mode: whole 16-byte stores);
           // the accepted token's entry is left out (zero) and the other probabilities are summed, so that
@@ -407,6 +422,7 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 
   // ---- partial results of this (row, chunk)
   const int64_t g = row0 + tid;
+  if (MODE == kFusedStore) return;
   if (MODE == kFusedBwd || MODE == kFusedPlanes) {
     if (g < M) a.part_s[g * a.n_chunks + chunk] = b_others;
     return;
@@ -696,6 +712,7 @@ static void ensure_lds_attrs() {
     set_lds_attr(k_fused_rows<16, kFusedStats>);
     set_lds_attr(k_fused_rows<1, kFusedBwd>);
     set_lds_attr(k_fused_rows<1, kFusedPlanes>);
+    set_lds_attr(k_fused_rows<1, kFusedStore>);
     set_lds_attr(k_fused_dh);
     attr_set = true;
   }
@@ -704,7 +721,9 @@ static void ensure_lds_attrs() {
 void launch_fused_rows(const FusedArgs &a, hipStream_t st) {
   ensure_lds_attrs();
   const int blocks = fused_grid(a);
-  if (a.plane_hi != nullptr)
+  if (a.store_rows != nullptr)
+    hipLaunchKernelGGL((k_fused_rows<1, kFusedStore>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
+  else if (a.plane_hi != nullptr)
     hipLaunchKernelGGL((k_fused_rows<1, kFusedPlanes>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);
   else if (a.grad_rows != nullptr)
     hipLaunchKernelGGL((k_fused_rows<1, kFusedBwd>), dim3(blocks), dim3(256), kFusedLdsBytes, st, a);

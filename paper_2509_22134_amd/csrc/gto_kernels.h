@@ -107,6 +107,9 @@ struct FusedArgs {
   // into two bf16 planes [M, V] (value = hi + lo; zero at the accepted token), the row operand of the
   // hidden-state gradient; part_s receives the sum of the other probabilities as in the backward mode
   uint16_t *plane_hi, *plane_lo;
+  // store mode (store_rows != null): the fp32 logits of row i of the processed rows go to store_rows[i, :V]
+  float *store_rows;
+  int64_t store_pitch;
 };
 
 // Hidden-state gradient dH = G . W of the fused variant: G = the two bf16 planes, W hidden-major.
@@ -161,6 +164,8 @@ void launch_gather_dot(const GatherDotArgs &a, hipStream_t st);
 struct TokenLossArgs {
   int R, d, k, V;
   int64_t row_stride;
+  int64_t root_stride;             // 0: root rows sit at slot (0,0) of [R, d, k, row_stride]; else elements between
+                                   // consecutive roots' rows in a compact [R, root_stride] layout
   const void *draft_logits, *target_logits;
   const float *d_lse, *t_lse;      // [R, d, k] statistics (entry of slot (0,0) is used)
   const float *weight;             // optional [R]

@@ -372,8 +372,9 @@ __global__ __launch_bounds__(256) void k_token_loss(TokenLossArgs a) {
   const int r = blockIdx.x;
   const float w = a.weight ? a.weight[r] : 1.f;
   const int64_t si = stat_index(r, 0, 0, a.d, a.k);
-  const T *__restrict__ drow = static_cast<const T *>(a.draft_logits) + si * a.row_stride;
-  const T *__restrict__ trow = static_cast<const T *>(a.target_logits) + si * a.row_stride;
+  const int64_t lo = a.root_stride ? (int64_t)r * a.root_stride : si * a.row_stride;
+  const T *__restrict__ drow = static_cast<const T *>(a.draft_logits) + lo;
+  const T *__restrict__ trow = static_cast<const T *>(a.target_logits) + lo;
   const float d_lse = a.d_lse[si], t_lse = a.t_lse[si];
   const int V = a.V;
   if (BWD) {

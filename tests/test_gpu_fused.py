@@ -223,6 +223,41 @@ def test_fused_hidden_state_gradient(gpu_device, R, d, k, g, hidden, V, flags):
     _say(f"  rows with a gradient: {int(live.sum())}, worst error / tolerance {float((err[live] / tol[live]).max()):.3f}")
 
 
+@pytest.mark.parametrize("R,V,hidden", [(24, 3000, 256), (300, 1032, 128)])
+def test_fused_token_level_loss(gpu_device, R, V, hidden):
+    """Eq. 13 for the fused variant: the root-row logits come from the matrix cores (fp32, error E),
+    so the cross-entropy and its gradient are compared within E-derived tolerances."""
+    d, k, g = 3, 4, 12
+    w = S.FusedWorkload("case", R=R, V=V, k=k, d=d, g=g, m=8, hidden=hidden, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.5, ref_sigma=0.05)
+    _say(f"fused token-level loss R={R} V={V} hidden={hidden}")
+    t = S.make_fused(w, gpu_device)
+    cfg = G.make_config(R=R, d=d, k=k, g=g, V=V, dtype=torch.bfloat16, group_size=1)
+    ws = torch.empty(G.gto_fused_workspace_bytes(cfg, hidden), dtype=torch.uint8, device=gpu_device)
+    ds = G.gto_fused_draft_row_stats(cfg, t["H_cur"], t["W_draft"], G.alloc_draft_stats(cfg, gpu_device), ws)
+    ts = G.gto_fused_target_row_stats(cfg, t["H_cur"], t["W_target"], G.alloc_target_stats(cfg, gpu_device), ws)
+    tws = torch.empty(G.gto_fused_token_loss_workspace_bytes(cfg, hidden), dtype=torch.uint8, device=gpu_device)
+    weight = torch.ones(R, device=gpu_device)
+    weight[1] = 0.0
+    loss_rows = torch.empty(R, device=gpu_device); loss = torch.empty(1, device=gpu_device)
+    inv = torch.empty(1, device=gpu_device); grad = torch.empty((R, V), device=gpu_device)
+    H = t["H_cur"].float().cpu().numpy()
+    Dn = O.fused_logits(H, t["W_draft"].double().cpu().numpy())
+    Tn = O.fused_logits(H, t["W_target"].double().cpu().numpy())
+    E = logit_error_bound(hidden, max(float(np.abs(Dn).max()), float(np.abs(Tn).max())))
+    for wt, wn in ((None, None), (weight, weight.cpu().numpy())):
+        G.gto_token_loss_fwd_fused(cfg, t["H_cur"], t["W_draft"], t["W_target"], ds, ts, wt, loss_rows, loss, inv, tws)
+        G.gto_token_loss_bwd_fused(cfg, ds, ts, wt, inv, 0.7, grad, tws)
+        torch.cuda.synchronize()
+        ref = O.token_loss(Dn, Tn, wn, 0.7)
+        np.testing.assert_allclose(loss_rows.cpu().numpy(), ref["loss_rows"], rtol=1e-5, atol=8 * E + 2e-6)
+        np.testing.assert_allclose(loss.item(), ref["loss"], rtol=1e-5, atol=8 * E + 2e-6)
+        gq = grad.cpu().numpy()
+        for r in range(R):
+            scale = np.abs(ref["grad"][r]).max()
+            assert np.abs(gq[r] - ref["grad"][r]).max() <= (1e-5 + 8 * E) * scale + 1e-12, r
+
+
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     _say("fused: chunk count / workgroup layout invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,

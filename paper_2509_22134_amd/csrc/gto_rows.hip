@@ -286,8 +286,11 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
 }
 
 // ------------------------------------------------------------------------------- backward
+// One workgroup of 16 waves per (root, step): only the few hundred rows on accepted paths do any work,
+// so the parallelism has to come from inside the row.
+constexpr int kBwdThreads = 1024;
 template <typename T, bool VEC>
-__global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
+__global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
   const int r = blockIdx.x / a.d;
   const int t = blockIdx.x - r * a.d;
   const int64_t rt = (int64_t)r * a.d + t;
@@ -353,10 +356,10 @@ __global__ __launch_bounds__(256) void k_ppo_bwd(PpoBwdArgs a) {
       out[i] = -coef * p;
     }
   }
-  __shared__ double s_part[256];
+  __shared__ double s_part[kBwdThreads];
   s_part[threadIdx.x] = (double)others;
   __syncthreads();
-  for (int off = 128; off >= 1; off >>= 1) {
+  for (int off = kBwdThreads / 2; off >= 1; off >>= 1) {
     if ((int)threadIdx.x < off) s_part[threadIdx.x] += s_part[threadIdx.x + off];
     __syncthreads();
   }
@@ -502,11 +505,11 @@ void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t 
 void launch_ppo_bwd(const PpoBwdArgs &a, int dtype, int blocks, hipStream_t st) {
   const bool vec = (a.V % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.grad_rows) & 15) == 0);
   if (dtype == 0) {
-    if (vec) hipLaunchKernelGGL((k_ppo_bwd<uint16_t, true>), dim3(blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_ppo_bwd<uint16_t, false>), dim3(blocks), dim3(256), 0, st, a);
+    if (vec) hipLaunchKernelGGL((k_ppo_bwd<uint16_t, true>), dim3(blocks), dim3(kBwdThreads), 0, st, a);
+    else hipLaunchKernelGGL((k_ppo_bwd<uint16_t, false>), dim3(blocks), dim3(kBwdThreads), 0, st, a);
   } else {
-    if (vec) hipLaunchKernelGGL((k_ppo_bwd<float, true>), dim3(blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_ppo_bwd<float, false>), dim3(blocks), dim3(256), 0, st, a);
+    if (vec) hipLaunchKernelGGL((k_ppo_bwd<float, true>), dim3(blocks), dim3(kBwdThreads), 0, st, a);
+    else hipLaunchKernelGGL((k_ppo_bwd<float, false>), dim3(blocks), dim3(kBwdThreads), 0, st, a);
   }
 }
 

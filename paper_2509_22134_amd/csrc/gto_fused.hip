@@ -382,9 +382,10 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
         } else
         if (ncols > 0) {
           // One pass over the 64 new logits: maximum, sum of exp2 against the reference exponent the
-          // row already has (st.c, not necessarily its maximum), and the top-k insertions.  The sum is
-          // re-referenced only when the maximum has moved far above st.c, and recomputed in the rare
-          // case that the old reference could have overflowed (or when the row has none yet).
+          // row already has (st.c, at most 2 below its maximum in the log2 domain), and the top-k
+          // insertions.  The sum is re-referenced when the maximum has moved more than that above st.c,
+          // and recomputed in the rare case that the old reference could have overflowed (or when the
+          // row has none yet).
           const bool have_ref = (st.m != neg_inf());
           const float c_ref = have_ref ? st.c : 0.f;
           float cm = neg_inf(), p = 0.f;
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
             const double s = have_ref ? st.s * (double)__builtin_amdgcn_exp2f(st.c - c_new) : 0.0;
             st.s = s + (double)p2;
             st.c = c_new;
-          } else if (over > 24.f) {
+          } else if (over > 1.f) {       // keep the dominant terms' exponents small: their rounding scales with |exponent|
             const float c_new = m_new * kLog2e;
             st.s = (st.s + (double)p) * (double)__builtin_amdgcn_exp2f(st.c - c_new);
             st.c = c_new;

@@ -16,6 +16,10 @@
  *   - Inputs are never modified.  Results are deterministic run to run.
  *   - Return value: GTO_OK (0) or a negative gto_status.  Arguments are validated on the
  *     host before anything is launched, so a failing call has no side effect.
+ *   - Calls may come from several host threads as long as the process-wide tuning knobs
+ *     (gto_set_waves_per_row, gto_set_fused_tuning) are not changed meanwhile; the optional
+ *     kernel timing is per calling thread.  Calls that share output buffers or a workspace
+ *     must be ordered by the caller (same stream, or events).
  *   - Logits are finite or -inf (probability 0).  A row that is entirely -inf, or holds a
  *     NaN, gives unspecified results for that root (no fault).
  *

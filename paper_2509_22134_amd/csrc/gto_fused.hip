@@ -705,9 +705,10 @@ static int fused_grid(const FusedArgs &a) {
   return ((pms * pcs + 7) / 8) * 8 * 32;
 }
 
+// the kernels that use the whole slab ring need the dynamic LDS limit raised once per process
+// (initialisation of a function-local static is thread-safe)
 static void ensure_lds_attrs() {
-  static bool attr_set = false;
-  if (!attr_set) {
+  static const bool done = [] {
     set_lds_attr(k_fused_rows<1, kFusedStats>);
     set_lds_attr(k_fused_rows<8, kFusedStats>);
     set_lds_attr(k_fused_rows<16, kFusedStats>);
@@ -715,8 +716,9 @@ static void ensure_lds_attrs() {
     set_lds_attr(k_fused_rows<1, kFusedPlanes>);
     set_lds_attr(k_fused_rows<1, kFusedStore>);
     set_lds_attr(k_fused_dh);
-    attr_set = true;
-  }
+    return true;
+  }();
+  (void)done;
 }
 
 void launch_fused_rows(const FusedArgs &a, hipStream_t st) {

@@ -59,6 +59,10 @@ def bench_fused(args, torch, S, G):
     flops = 2.0 * w.R * w.rho * w.V * w.hidden
     dom_ms = kernels[dom]["avg_ms"]
     achieved = flops / (dom_ms * 1e-3) / 1e12
+    traffic = None               # HBM-side bytes per launch of the dominant kernel, from the rocprofv3 counter runs
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath) and not args.roots:
+        traffic = json.load(open(tpath)).get(f"{dom}:{w.name}")
     out = {
         "metric": "draft trees scored/sec (build+reward+PPO), fused LM head, V=%d" % w.V,
         "value": 2 * w.R / (dt / args.steps), "unit": "trees/s", "n_gpus": 1, "steps": args.steps,
@@ -70,7 +74,7 @@ def bench_fused(args, torch, S, G):
                    "target_rows_multiplied": [int(path.buf[x]["tree"]["slot_need"].sum().item()) for x in ("cur", "ref")],
                    "draft_rows": w.R * w.rho},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
                      "flops_per_launch": flops, "avg_launch_ms": dom_ms},
         "kernels": kernels,
     }

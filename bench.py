@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel (4 GiB) so that HBM counters can be scaled")
     ap.add_argument("--group-size", type=int, default=0, help="override m, the roots per advantage group (0 = workload's)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into a HIP graph and time its replays (kernel durations then come from one "
+                         "eager pass after the timed region)")
     ap.add_argument("--one-stream", action="store_true", help="chunked workloads: issue every chunk on one stream")
     ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
@@ -184,6 +187,15 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    eager_step = step
+    if args.graph and n_lanes == 1:
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hip_graph):
+            eager_step()
+        step = hip_graph.replay
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
     if args.calibrate_copy:
         src = torch.ones((1 << 30,), dtype=torch.int32, device=dev)      # 4 GiB read + 4 GiB written
         dst = torch.empty_like(src)
@@ -191,16 +203,17 @@ def main():
             G.gto_calibration_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
-    G.gto_profile_enable(n_lanes == 1)
+    use_graph = args.graph and n_lanes == 1
+    G.gto_profile_enable(n_lanes == 1 and not use_graph)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     G.gto_profile_enable(False)
-    if n_lanes > 1:
-        # kernels of the two streams overlap in the timed region, so their own durations are taken from one
-        # more pass that issues every chunk on one stream
+    if n_lanes > 1 or use_graph:
+        # kernels of the two streams overlap in the timed region (and a graph replay carries no events), so the
+        # kernels' own durations are taken from one more eager pass that issues every chunk on one stream
         G.gto_profile_enable(True)
         for _ in range(n_chunks):
             path.step(tens["D_cur"], tens["T_cur"], tens.get("D_ref"), tens.get("T_ref"))
@@ -238,7 +251,8 @@ def main():
                                f"{w.dtype} logits, " + ("full path, current + reference tree per root"
                                                        if w.full_path else "reward only"),
                    "chunks": n_chunks, "streams": n_lanes,
-                   "kernel_durations": "timed region" if n_lanes == 1 else "separate one-stream pass after the timed region",
+                   "kernel_durations": "timed region" if (n_lanes == 1 and not use_graph) else "separate one-stream pass after the timed region",
+                   "hip_graph": bool(use_graph),
                    "waves_per_row": args.waves or "auto",
                    "target_rows": "all used slots" if args.no_prune else "only slots with a kept child",
                    "target_rows_streamed_per_chunk": target_rows, "draft_rows_per_chunk": n_models * R * w.rho},

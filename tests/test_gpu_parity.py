@@ -333,6 +333,41 @@ def test_sampled_reading_of_the_longest_accepted_sequence(gpu_device, name, R, V
     _compare_ppo(w, tens, path)
 
 
+def test_step_can_be_captured_in_a_hip_graph(gpu_device):
+    """The library allocates nothing, clears nothing with memset and never synchronises, so one step can
+    be recorded into a HIP graph.  Every replay (with the inputs changed in place and eager work and
+    synchronisations in between) must reproduce the eager results bit for bit."""
+    _say("graph capture of one step")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=9000)
+    tens = S.make_logits(w, gpu_device)
+    other = S.make_logits(S.scaled(w, seed=w.seed + 17), gpu_device)
+    mk = lambda: GtoPath(R=16, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=gpu_device,
+                         eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=G.GTO_FLAG_GRAD_ZERO_FILL)
+    eager, graphed = mk(), mk()
+    buf = {n: t.clone() for n, t in tens.items()}                  # the graph reads these buffers
+    graphed.step(buf["D_cur"], buf["T_cur"], buf["D_ref"], buf["T_ref"])     # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        graphed.step(buf["D_cur"], buf["T_cur"], buf["D_ref"], buf["T_ref"])
+    for it, src in enumerate((tens, other, tens, other)):
+        for n in buf:
+            buf[n].copy_(src[n])
+        graph.replay()
+        eager.step(src["D_cur"], src["T_cur"], src["D_ref"], src["T_ref"])
+        torch.cuda.synchronize()
+        for tag in ("cur", "ref"):
+            for grp in ("dstats", "pool", "tree", "tstats", "reward"):
+                for n, x in eager.buf[tag][grp].items():
+                    if grp == "tstats":        # entries of slots without a kept child keep whatever they held
+                        continue
+                    assert torch.equal(x, graphed.buf[tag][grp][n]), (it, tag, grp, n)
+        for n, x in eager.ppo.items():
+            assert torch.equal(x, graphed.ppo[n]), (it, n)
+        assert torch.equal(eager.adv, graphed.adv), it
+        assert torch.equal(eager.grad_slot, graphed.grad_slot) and torch.equal(eager.grad_rows, graphed.grad_rows), it
+
+
 def test_bitwise_deterministic(gpu_device):
     _say("determinism")
     w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=16000)

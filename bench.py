@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record the step into a HIP graph and time its replays (kernel durations then come from one "
                          "eager pass after the timed region)")
+    ap.add_argument("--chunk-roots", type=int, default=0,
+                    help="process the batch in chunks of this many roots (alternating between two streams)")
     ap.add_argument("--one-stream", action="store_true", help="chunked workloads: issue every chunk on one stream")
     ap.add_argument("--cpu-roots", type=int, default=24, help="roots given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
@@ -155,6 +157,8 @@ def main():
         w = S.scaled(w, m=args.group_size)
     if args.waves:
         G.gto_set_waves_per_row(args.waves)
+    if args.chunk_roots:
+        w = S.scaled(w, chunk_roots=args.chunk_roots)
     R = w.chunk_roots or w.R
     n_chunks = w.R // R
     wr = S.scaled(w, R=R)

@@ -28,6 +28,11 @@ Optimization for Speculative Decoding"):
     longest accepted sequence, Eq. 12 clipped surrogate; Algorithm 1.
   * Eq. 13 and App. B.2: token-level cross-entropy from the target to the draft distribution.
   * App. B.1/B.3: k = 10, g = 60, depth 7, eta = 1, m = 8.
+  * Sec. 4 "Metrics": evaluation at temperatures 0 and 1; the temperature-1 reading of the longest
+    accepted sequence (sampled_path) is the lossless acceptance rule for deterministically chosen
+    candidates, whose expectation is the node-sum of App. A Eq. (2).
+  * Fused LM-head variant: logits = hidden . W^T (fused_logits); the hidden-state gradient is the
+    chain rule through that product (ppo_surrogate_bwd_dh).
 
 Readings where the paper is silent (each is repeated next to the code it affects):
   tie-breaks are lowest token id / lowest pool index; g counts kept nodes (root

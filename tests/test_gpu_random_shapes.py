@@ -1,0 +1,85 @@
+"""Seeded sweep of random small shapes (branching, depth, budget, vocabulary, padding, dtype, group size,
+input recipe) through the same staged GPU-vs-oracle comparison as test_gpu_parity.py / test_gpu_fused.py."""
+import random
+
+import pytest
+import torch
+
+import gto_synth as S
+import paper_2509_22134_amd as G
+import test_gpu_fused as F
+import test_gpu_parity as T
+
+pytestmark = pytest.mark.gpu
+
+
+def _streaming_case(rng, it):
+    dtype = rng.choice(["bf16", "f32"])
+    al = 8 if dtype == "bf16" else 4
+    k = rng.choice([1, 2, 3, 4, 5, 7, 8, 10, 12, 16, 20, 32, 33, 64])
+    d = rng.choice([1, 2, 3, 4, 5, 6, 7])
+    while k + (d - 1) * k * k > 4096:
+        d -= 1
+    C = k + (d - 1) * k * k
+    g = rng.choice([1, 2, max(1, C // 3), max(1, C - 1), C, C + 3, 60])
+    m = rng.choice([1, 2, 4, 8, 24])
+    R = m * rng.choice([1, 2, 3])
+    V = max(k, rng.choice([k, 17, 64, 100, 257, 1000, 2049, 3000, 4097, 8200]))
+    pad = ((V + al - 1) // al) * al
+    recipe = rng.choice(["zipf_peaks", "gauss_plant_target", "gauss_plant_shared"])
+    w = S.Workload(f"rnd{it}", R=R, V=pad, k=k, d=d, g=g, m=m, dtype=dtype, recipe=recipe, seed=1000 + it,
+                   n_peaks=min(32, max(1, V // 4)))
+    return w, V, pad, rng.choice([0, G.GTO_FLAG_GRAD_ZERO_FILL])
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_shapes_streaming(gpu_device, seed):
+    rng = random.Random(seed)
+    for it in range(12):
+        w, V, pad, flags = _streaming_case(rng, it)
+        T._say(f"random shape {seed}/{it}: dtype={w.dtype} R={w.R} d={w.d} k={w.k} g={w.g} m={w.m} V={V} "
+               f"pad={pad} recipe={w.recipe} flags={flags}")
+        tens = S.make_logits(w, gpu_device)
+        if pad != V:
+            for t in tens.values():
+                t[..., V:] = 77.0
+        stride = pad if pad != V else None
+        path = T._run_full(w, tens, gpu_device, row_stride=stride, V=V, flags=flags)
+        T._compare_all(w, tens, path, V=V)
+        T._compare_ppo(w, tens, path, flags=flags)
+        # pruning changes nothing but the target rows streamed
+        p2 = T._run_full(w, tens, gpu_device, row_stride=stride, V=V, flags=flags | G.GTO_FLAG_TARGET_PRUNE)
+        for tag in ("cur", "ref"):
+            for grp in ("tree", "reward"):
+                for name, x in path.buf[tag][grp].items():
+                    assert torch.equal(x, p2.buf[tag][grp][name]), (it, tag, grp, name)
+        for name, x in path.ppo.items():
+            assert torch.equal(x, p2.ppo[name]), (it, name)
+        live = path.grad_slot >= 0
+        assert torch.equal(path.grad_slot, p2.grad_slot) and torch.equal(path.grad_rows[live], p2.grad_rows[live])
+
+
+def test_random_shapes_fused(gpu_device):
+    rng = random.Random(1)
+    try:
+        for it in range(10):
+            k = rng.choice([1, 2, 4, 5, 8, 10, 16])
+            d = rng.choice([1, 2, 3, 4])
+            C = k + (d - 1) * k * k
+            g = rng.choice([1, max(1, C // 3), C, C + 2, 20])
+            m = rng.choice([1, 2, 8])
+            R = m * rng.choice([1, 2, 5])
+            hidden = rng.choice([64, 128, 192, 256, 448])
+            V = max(((k + 7) // 8) * 8, rng.choice([8, 64, 200, 256, 1032, 2048, 3000, 4104]))
+            corr = rng.choice([0.0, 0.8, 0.95])
+            w = S.FusedWorkload(f"rnd{it}", R=R, V=V, k=k, d=d, g=g, m=m, hidden=hidden, h_scale=3.0, w_sigma=0.05,
+                                w_corr=corr, ref_sigma=0.05, seed=5000 + it)
+            nc = rng.choice([0, 1, 3])
+            T._say(f"random fused shape {it}: R={R} d={d} k={k} g={g} m={m} hidden={hidden} V={V} corr={corr} chunks={nc}")
+            t = S.make_fused(w, gpu_device)
+            G.gto_set_fused_tuning(nc, True)
+            path = F._run(w, t, gpu_device)
+            L, _ = F._compare_fused(w, t, path, list(range(R)))
+            T._compare_ppo(w, L, path)
+    finally:
+        G.gto_set_fused_tuning(0, True)

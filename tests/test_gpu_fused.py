@@ -258,6 +258,40 @@ def test_fused_token_level_loss(gpu_device, R, V, hidden):
             assert np.abs(gq[r] - ref["grad"][r]).max() <= (1e-5 + 8 * E) * scale + 1e-12, r
 
 
+def test_fused_step_can_be_captured_in_a_hip_graph(gpu_device):
+    _say("fused: graph capture of one step")
+    w = S.FusedWorkload("case", R=24, V=3072, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
+                        w_corr=0.9, ref_sigma=0.05)
+    t = S.make_fused(w, gpu_device)
+    t2 = S.make_fused(S.scaled(w, seed=w.seed + 3), gpu_device)
+    mk = lambda: GtoFusedPath(R=w.R, d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m, device=gpu_device,
+                              eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=G.GTO_FLAG_GRAD_ZERO_FILL,
+                              want_dh=True)
+    eager, graphed = mk(), mk()
+    buf = {n: x.clone() for n, x in t.items()}
+    hv = buf["W_draft"].t().contiguous()
+    graphed.step(buf["H_cur"], buf["H_ref"], buf["W_draft"], buf["W_target"], W_draft_hv=hv)    # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        graphed.step(buf["H_cur"], buf["H_ref"], buf["W_draft"], buf["W_target"], W_draft_hv=hv)
+    for it, src in enumerate((t, t2, t)):
+        for n in buf:
+            buf[n].copy_(src[n])
+        hv.copy_(src["W_draft"].t())
+        graph.replay()
+        eager.step(src["H_cur"], src["H_ref"], src["W_draft"], src["W_target"], W_draft_hv=src["W_draft"].t().contiguous())
+        torch.cuda.synchronize()
+        for tag in ("cur", "ref"):
+            for grp in ("dstats", "pool", "tree", "tstats", "reward"):
+                for n, x in eager.buf[tag][grp].items():
+                    assert torch.equal(x, graphed.buf[tag][grp][n]), (it, tag, grp, n)
+        for n, x in eager.ppo.items():
+            assert torch.equal(x, graphed.ppo[n]), (it, n)
+        assert torch.equal(eager.grad_slot, graphed.grad_slot) and torch.equal(eager.grad_rows, graphed.grad_rows), it
+        assert torch.equal(eager.dh_slot, graphed.dh_slot) and torch.equal(eager.dh_rows, graphed.dh_rows), it
+
+
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     _say("fused: chunk count / workgroup layout invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,

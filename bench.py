@@ -163,8 +163,6 @@ def main():
         w = S.scaled(w, R=args.roots)
     if args.group_size:
         w = S.scaled(w, m=args.group_size)
-    if args.waves:
-        G.gto_set_waves_per_row(args.waves)
     if args.chunk_roots:
         w = S.scaled(w, chunk_roots=args.chunk_roots)
     R = w.chunk_roots or w.R
@@ -177,7 +175,8 @@ def main():
     n_lanes = 2 if (n_chunks > 1 and not args.one_stream) else 1
     paths = [GtoPath(R=R, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=dev,
                      eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, full_path=w.full_path,
-                     flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE) for _ in range(n_lanes)]
+                     flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE, waves_per_row=args.waves)
+             for _ in range(n_lanes)]
     path = paths[0]
     streams = [torch.cuda.Stream(device=dev) for _ in range(n_lanes)] if n_lanes > 1 else [None]
 

@@ -16,12 +16,14 @@
  *   - Inputs are never modified.  Results are deterministic run to run.
  *   - Return value: GTO_OK (0) or a negative gto_status.  Arguments are validated on the
  *     host before anything is launched, so a failing call has no side effect.
- *   - Calls may come from several host threads as long as the process-wide tuning knobs
- *     (gto_set_waves_per_row, gto_set_fused_tuning) are not changed meanwhile; the optional
- *     kernel timing is per calling thread.  Calls that share output buffers or a workspace
- *     must be ordered by the caller (same stream, or events).
+ *   - The library keeps no mutable process-wide state: every tuning choice travels in `cfg`.
+ *     Calls may come from several host threads; the optional kernel timing is per calling
+ *     thread.  Calls that share output buffers or a workspace must be ordered by the caller
+ *     (same stream, or events).
  *   - Logits are finite or -inf (probability 0).  A row that is entirely -inf, or holds a
- *     NaN, gives unspecified results for that root (no fault).
+ *     NaN, gives unspecified VALUES for that root, but never a fault: every token id the
+ *     library writes is in [0, V), every index it follows is range-checked, and the other
+ *     roots are not affected.
  *
  * Shapes.  R roots, d levels, k branching, g kept nodes, V vocabulary,
  * C = k + (d-1) k^2 generated candidates per root.
@@ -84,6 +86,15 @@ typedef struct gto_config {
   float grad_scale;     /* upstream dL/dL_GTO (the paper's omega = 0.5 in Eq. 13)          */
   int32_t flags;        /* GTO_FLAG_*                                                      */
   int32_t path_mode;    /* GTO_PATH_*: which sequence the surrogate is taken along           */
+  /* Tuning, per call; 0 everywhere = the library's own choice.  Results never depend on these
+   * (bit for bit for ids; the fused variant's floats within its usual tolerance).            */
+  int32_t waves_per_row;  /* wavefronts sharing one logits row in the row kernels: 0 (chosen per
+                             launch from V and the number of rows), 1, 2, 4 or 8; else GTO_E_MODE */
+  int32_t fused_chunks;   /* fused variant: vocabulary chunks per block of 256 rows, 0 (chosen per
+                             launch) .. 64; else GTO_E_MODE.  Sizes the fused workspace.        */
+  int32_t fused_layout;   /* fused variant: 0 = workgroups laid out in per-XCD patches of 4 row
+                             blocks x 8 chunks (default), 1 = plain row-major order             */
+  int32_t reserved;       /* must be 0                                                          */
 } gto_config;
 
 /* Row statistics of a draft-logits tensor.  Entries of padding slots are not written. */
@@ -171,7 +182,9 @@ int gto_target_row_stats(const gto_config *cfg, const void *target_logits,
  * the score): gto_draft_row_stats, then the level-by-level expansion.  A candidate's global
  * acceptance score is score(parent) + log-probability (fp32 add; root = 0); at every level
  * below the last the k best of the k^2 children (score descending, pool index ascending)
- * become the next level's slots, in that order. */
+ * become the next level's slots, in that order.  `workspace` is unused by this call (no scratch
+ * memory is needed): it may be NULL and workspace_bytes 0; the pair is there so that every one of
+ * the six calls has the same shape. */
 int gto_expand_tree(const gto_config *cfg, const void *draft_logits,
                     const gto_draft_stats *stats_out, const gto_pool *pool_out,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -188,7 +201,8 @@ int gto_select_topg(const gto_config *cfg, const gto_pool *pool, const gto_tree 
 
 /* Draft Tree Reward (Eq. 2-5; Max / Mean of the aggregation ablation; App. A Eq. (2) as
  * `nodesum`) and the longest accepted sequence under greedy target verification (Sec. 3.2,
- * Algorithm 1; App. A case T = 0).  Runs gto_target_row_stats, then the per-root scan. */
+ * Algorithm 1; App. A case T = 0).  Runs gto_target_row_stats, then the per-root scan.
+ * `workspace` is unused by this call: it may be NULL and workspace_bytes 0. */
 int gto_tree_reward(const gto_config *cfg, const gto_tree *tree, const void *target_logits,
                     const gto_target_stats *stats_out, const gto_reward *reward_out,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
@@ -324,24 +338,19 @@ int gto_token_loss_bwd_fused(const gto_config *cfg, const gto_draft_stats *draft
                              const float *inv_count, float grad_scale, float *grad_rows0, const void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
-/* Tuning knob of the fused kernels: vocabulary chunks per row block (0 = per-launch choice) and
- * whether workgroups are laid out in per-XCD patches (default 1).  Process-wide. */
-int gto_set_fused_tuning(int n_chunks, int xcd_patches);
-
 /* Measurement aid, not part of the method: copies `bytes` (a multiple of 16; both device pointers
  * 16-byte aligned, non-overlapping) with a plain kernel.  Hardware HBM counters of the row kernels
  * are scaled by what the same counters report for this copy of known size. */
 int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 
-/* Tuning knob: wavefronts that share one logits row in the row kernels (1, 2, 4 or 8; any other
- * value restores the default, a per-launch choice from V and the number of rows).  Process-wide;
- * returns the value in effect, 0 meaning the per-launch choice. */
-int gto_set_waves_per_row(int waves);
-
 /* Optional per-kernel timing.  While enabled, every kernel launch of the calling thread is
- * bracketed by HIP events on its stream.  gto_profile_read synchronises those events and
- * returns, for up to `cap` distinct kernels, the name, the number of launches and the summed
- * duration in milliseconds since the last read; it returns the number of kernels written. */
+ * bracketed by two HIP events recorded on its stream; the events come from a per-thread pool
+ * that gto_profile_enable(1) fills (the only place where events are created), so nothing is
+ * created inside a timed region.  At most 16384 launches are kept between two reads; further
+ * ones are not timed.  gto_profile_read synchronises the recorded events, returns them to the
+ * pool and reports, for up to `cap` distinct kernels, the name, the number of launches and the
+ * summed duration in milliseconds since the last read; it returns the number of kernels written.
+ * gto_profile_enable(0) stops recording; the pool lives until the thread ends. */
 int gto_profile_enable(int on);
 int gto_profile_read(const char **names, int32_t *launches, double *total_ms, int cap);
 

@@ -14,7 +14,7 @@ GTO_FLAG_GRAD_ZERO_FILL = 1
 GTO_FLAG_TARGET_PRUNE = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.environ.get("GTO_LIB_PATH") or os.path.join(_HERE, "libgto.so")   # override: tuning builds
+_LIB_PATH = os.path.join(_HERE, "libgto.so")
 _lib = None
 
 
@@ -28,7 +28,9 @@ class gto_config(C.Structure):
     _fields_ = [("R", C.c_int32), ("d", C.c_int32), ("k", C.c_int32), ("g", C.c_int32), ("V", C.c_int32),
                 ("dtype", C.c_int32), ("row_stride", C.c_int64), ("group_size", C.c_int32),
                 ("reward_mode", C.c_int32), ("eta", C.c_float), ("eps", C.c_float), ("delta", C.c_float),
-                ("grad_scale", C.c_float), ("flags", C.c_int32), ("path_mode", C.c_int32)]
+                ("grad_scale", C.c_float), ("flags", C.c_int32), ("path_mode", C.c_int32),
+                ("waves_per_row", C.c_int32), ("fused_chunks", C.c_int32), ("fused_layout", C.c_int32),
+                ("reserved", C.c_int32)]
 
     @property
     def C(self):
@@ -101,7 +103,6 @@ def lib():
     L.gto_fused_workspace_bytes.argtypes = [cfgp, C.c_int32, P(SZ)]
     L.gto_fused_draft_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), VP, VP, SZ, VP]
     L.gto_fused_target_row_stats.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_target_stats), VP, SZ, VP]
-    L.gto_set_fused_tuning.argtypes = [C.c_int, C.c_int]
     L.gto_expand_tree_fused.argtypes = [cfgp, VP, C.c_int32, VP, P(gto_draft_stats), P(gto_pool), VP, SZ, VP]
     L.gto_tree_reward_fused.argtypes = [cfgp, P(gto_tree), VP, C.c_int32, VP, P(gto_target_stats), P(gto_reward),
                                         VP, SZ, VP]
@@ -112,15 +113,14 @@ def lib():
     L.gto_fused_dh_workspace_bytes.argtypes = [cfgp, C.c_int32, P(C.c_size_t)]
     L.gto_ppo_surrogate_bwd_fused_dh.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, C.c_int32, VP, VP,
                                                  P(gto_draft_stats), VP, VP, VP, SZ, VP]
-    L.gto_set_waves_per_row.argtypes = [C.c_int]
     L.gto_profile_enable.argtypes = [C.c_int]
     L.gto_profile_read.argtypes = [P(C.c_char_p), P(C.c_int32), P(C.c_double), C.c_int]
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
-                 "gto_set_waves_per_row", "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
+                 "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
-                 "gto_set_fused_tuning", "gto_expand_tree_fused", "gto_tree_reward_fused",
+                 "gto_expand_tree_fused", "gto_tree_reward_fused",
                  "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused",
                  "gto_fused_dh_workspace_bytes", "gto_ppo_surrogate_bwd_fused_dh",
                  "gto_fused_token_loss_workspace_bytes", "gto_token_loss_fwd_fused", "gto_token_loss_bwd_fused"):
@@ -130,11 +130,12 @@ def lib():
 
 
 def make_config(*, R, d, k, g, V, dtype, row_stride=None, group_size=1, reward_mode=GTO_REWARD_LSE,
-                eta=1.0, eps=0.2, delta=1e-6, grad_scale=1.0, flags=0, path_mode=0) -> gto_config:
+                eta=1.0, eps=0.2, delta=1e-6, grad_scale=1.0, flags=0, path_mode=0, waves_per_row=0,
+                fused_chunks=0, fused_layout=0) -> gto_config:
     if isinstance(dtype, torch.dtype):
         dtype = GTO_BF16 if dtype == torch.bfloat16 else GTO_F32
     return gto_config(R, d, k, g, V, dtype, V if row_stride is None else row_stride, group_size, reward_mode,
-                      eta, eps, delta, grad_scale, flags, path_mode)
+                      eta, eps, delta, grad_scale, flags, path_mode, waves_per_row, fused_chunks, fused_layout, 0)
 
 
 # ------------------------------------------------------------------ output containers (torch = memory only)
@@ -388,10 +389,6 @@ def gto_ppo_surrogate_bwd_fused_dh(cfg, tree_cur, path_cur, fwd, hidden_cur, w_d
     return dh_rows, grad_slot
 
 
-def gto_set_fused_tuning(n_chunks: int = 0, xcd_patches: bool = True) -> None:
-    _check(lib().gto_set_fused_tuning(int(n_chunks), 1 if xcd_patches else 0), "gto_set_fused_tuning")
-
-
 def gto_token_loss_fwd(cfg, draft_logits, target_logits, draft_stats, target_stats, weight, loss_rows, loss,
                        inv_count, stream=None):
     ds, ts = _pack(gto_draft_stats, _DRAFT, draft_stats), _pack(gto_target_stats, _TARGET, target_stats)
@@ -441,10 +438,6 @@ def gto_calibration_copy(src, dst, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib().gto_calibration_copy(_dp(src), _dp(dst), nbytes, _stream(stream)), "gto_calibration_copy")
     return dst
-
-
-def gto_set_waves_per_row(waves: int) -> int:
-    return lib().gto_set_waves_per_row(int(waves))
 
 
 def gto_profile_enable(on: bool) -> None:

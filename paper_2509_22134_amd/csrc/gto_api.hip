@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/gto.h"
@@ -21,28 +22,52 @@ int hip_status() {
 }
 
 // ------------------------------------------------------------------------- profiling
+// Per calling thread: a pool of event pairs filled by gto_profile_enable(1) and recycled by
+// gto_profile_read, so that a launch under profiling only records two events.
 struct ProfRecord {
   const char *name;
   hipEvent_t start, stop;
 };
-thread_local bool t_prof_on = false;
-thread_local std::vector<ProfRecord> t_prof;
+constexpr size_t kProfInitialPairs = 1024, kProfMaxRecords = 16384;
+struct ProfState {
+  bool on = false;
+  std::vector<ProfRecord> used;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> free_pairs;
+  size_t created = 0;
+  bool grow(size_t n) {
+    for (size_t i = 0; i < n && created < kProfMaxRecords; ++i) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return false;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return false; }
+      free_pairs.emplace_back(a, b);
+      ++created;
+    }
+    return true;
+  }
+  ~ProfState() {
+    // events are left to the runtime's own teardown: the device may already be gone when a thread ends
+  }
+};
+thread_local ProfState t_prof;
 
 struct ProfScope {
   hipStream_t st;
   bool on;
   ProfRecord rec;
-  ProfScope(const char *name, hipStream_t s) : st(s), on(t_prof_on) {
+  ProfScope(const char *name, hipStream_t s) : st(s), on(t_prof.on) {
     if (!on) return;
+    if (t_prof.free_pairs.empty() && !t_prof.grow(256)) { on = false; return; }
+    if (t_prof.free_pairs.empty()) { on = false; return; }      // cap reached: this launch is not timed
     rec.name = name;
-    (void)hipEventCreate(&rec.start);
-    (void)hipEventCreate(&rec.stop);
+    rec.start = t_prof.free_pairs.back().first;
+    rec.stop = t_prof.free_pairs.back().second;
+    t_prof.free_pairs.pop_back();
     (void)hipEventRecord(rec.start, st);
   }
   ~ProfScope() {
     if (!on) return;
     (void)hipEventRecord(rec.stop, st);
-    t_prof.push_back(rec);
+    t_prof.used.push_back(rec);
   }
 };
 
@@ -50,6 +75,21 @@ struct ProfScope {
 constexpr int kMaxK = 64, kMaxD = 32, kMaxPool = 4096;
 
 int elem_size(int dtype) { return dtype == GTO_BF16 ? 2 : 4; }
+
+// Tests on the bit pattern: this file is compiled with the same floating-point flags as the kernels
+// (NaNs not honoured), so a comparison is not a reliable way to reject a NaN argument here.
+bool finite_at_least(float x, bool allow_zero) {
+  uint32_t u;
+  memcpy(&u, &x, sizeof u);
+  if ((u & 0x7f800000u) == 0x7f800000u) return false;          // inf or NaN
+  if ((u & 0x7fffffffu) == 0u) return allow_zero;               // +0 or -0
+  return (u & 0x80000000u) == 0u;                               // positive
+}
+bool is_finite(float x) {
+  uint32_t u;
+  memcpy(&u, &x, sizeof u);
+  return (u & 0x7f800000u) != 0x7f800000u;
+}
 
 int check_cfg(const gto_config *c, bool need_group) {
   if (!c) return GTO_E_NULL;
@@ -63,7 +103,14 @@ int check_cfg(const gto_config *c, bool need_group) {
   if ((int64_t)c->R * rho > 2147483647ll || (int64_t)c->R * c->d > 2147483647ll) return GTO_E_SHAPE;
   if ((c->row_stride * elem_size(c->dtype)) % 16 != 0) return GTO_E_ALIGN;
   if (c->reward_mode < GTO_REWARD_LSE || c->reward_mode > GTO_REWARD_NODESUM) return GTO_E_MODE;
-  if (!(c->eta > 0.f) || !(c->eps >= 0.f) || !(c->delta >= 0.f)) return GTO_E_MODE;
+  if (!finite_at_least(c->eta, false) || !finite_at_least(c->eps, true) || !finite_at_least(c->delta, true) ||
+      !is_finite(c->grad_scale))
+    return GTO_E_MODE;
+  const int wpr = c->waves_per_row;
+  if (!(wpr == 0 || wpr == 1 || wpr == 2 || wpr == 4 || wpr == 8)) return GTO_E_MODE;
+  if (c->fused_chunks < 0 || c->fused_chunks > 64 || (c->fused_layout != 0 && c->fused_layout != 1) ||
+      c->reserved != 0)
+    return GTO_E_MODE;
   if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L && c->path_mode != GTO_PATH_SAMPLED)
     return GTO_E_MODE;
   if (need_group && (c->group_size < 1 || c->R % c->group_size != 0)) return GTO_E_SHAPE;
@@ -135,6 +182,7 @@ void run_draft_rows(const gto_config *c, const void *logits, const gto_draft_sta
   a.logits = logits;
   a.row_stride = c->row_stride;
   a.V = c->V; a.d = c->d; a.kslots = c->k; a.ktop = c->k; a.rho = rows_per_root(c);
+  a.waves = c->waves_per_row;
   a.path_slot = nullptr;
   a.row_max = s->row_max; a.row_lse = s->row_lse; a.top_tok = s->top_tok; a.top_logp = s->top_logp;
   ProfScope ps("row_stats_draft", st);
@@ -147,6 +195,7 @@ void run_target_rows(const gto_config *c, const void *logits, const gto_target_s
   a.logits = logits;
   a.row_stride = c->row_stride;
   a.V = c->V; a.d = c->d; a.kslots = c->k; a.ktop = 1; a.rho = rows_per_root(c);
+  a.waves = c->waves_per_row;
   a.path_slot = nullptr;
   a.row_need = row_need;
   a.row_max = s->t_max; a.row_lse = s->t_lse; a.top_tok = s->t_argmax; a.top_logp = nullptr;
@@ -168,7 +217,7 @@ void run_expand(const gto_config *c, const gto_draft_stats *s, const gto_pool *p
 void run_reward(const gto_config *c, const gto_tree *t, const void *logits, const gto_target_stats *s,
                 const gto_reward *w, hipStream_t st) {
   gto::RewardArgs a{};
-  a.R = c->R; a.d = c->d; a.k = c->k; a.g = c->g; a.dtype = c->dtype; a.reward_mode = c->reward_mode;
+  a.R = c->R; a.d = c->d; a.k = c->k; a.g = c->g; a.V = c->V; a.dtype = c->dtype; a.reward_mode = c->reward_mode;
   a.path_mode = c->path_mode;
   a.row_stride = c->row_stride; a.eta = c->eta;
   a.target_logits = logits; a.t_lse = s->t_lse; a.t_argmax = s->t_argmax; a.accept_u = w->accept_u;
@@ -180,10 +229,54 @@ void run_reward(const gto_config *c, const gto_tree *t, const void *logits, cons
   gto::launch_reward(a, st);
 }
 
+int check_ppo_fwd_args(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                       const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
+                       const void *ref_logits_on_cur, const float *adv, const gto_ppo *out) {
+  GTO_TRY(check_cfg(cfg, true));
+  GTO_TRY(check_logits(draft_logits_cur));
+  GTO_TRY(check_logits(ref_logits_on_cur));
+  GTO_TRY(check_tree(tree_cur));
+  GTO_TRY(check_reward(path_cur));
+  if (!draft_stats_cur || !draft_stats_cur->row_lse || !adv) return GTO_E_NULL;
+  GTO_TRY(check_ppo(out));
+  return GTO_OK;
+}
+
+// Eq. 11-12.  The reference rows' log-sum-exp comes either from statistics of the whole tensor
+// (`ref_lse_by_slot`, [R, d, k]) or is computed here for the rows on the accepted paths into
+// `lse_by_step` ([R, d] floats of scratch memory).
+void run_ppo_fwd(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                 const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur, const void *ref_logits_on_cur,
+                 const float *ref_lse_by_slot, float *lse_by_step, const float *adv, const gto_ppo *out,
+                 hipStream_t st) {
+  if (!ref_lse_by_slot) {
+    gto::RowStatsArgs a{};
+    a.logits = ref_logits_on_cur;
+    a.row_stride = cfg->row_stride;
+    a.V = cfg->V; a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.rho = rows_per_root(cfg);
+    a.waves = cfg->waves_per_row;
+    a.path_slot = path_cur->path_slot;
+    a.row_max = nullptr; a.row_lse = lse_by_step; a.top_tok = nullptr; a.top_logp = nullptr;
+    ProfScope ps("row_stats_ref_path", st);
+    gto::launch_row_stats(a, cfg->dtype, cfg->R * cfg->d, st);
+  }
+  gto::PpoFwdArgs a{};
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.m = cfg->group_size; a.dtype = cfg->dtype; a.V = cfg->V;
+  a.row_stride = cfg->row_stride; a.eps = cfg->eps; a.grad_scale = cfg->grad_scale;
+  a.draft_logits = draft_logits_cur; a.ref_logits = ref_logits_on_cur;
+  a.draft_lse = draft_stats_cur->row_lse;
+  a.ref_lse = ref_lse_by_slot ? ref_lse_by_slot : lse_by_step;
+  a.ref_lse_by_step = ref_lse_by_slot ? 0 : 1;
+  a.sel_tok = tree_cur->sel_tok; a.path_len = path_cur->path_len; a.path_node = path_cur->path_node;
+  a.path_slot = path_cur->path_slot; a.adv = adv;
+  a.logM = out->logM; a.logM0 = out->logM0; a.ratio = out->ratio; a.term = out->term; a.coef = out->coef;
+  a.loss_group = out->loss_group; a.loss = out->loss; a.active = out->active;
+  ProfScope ps("ppo_fwd", st);
+  gto::launch_ppo_fwd(a, st);
+}
+
 // ------------------------------------------------------------------------- fused LM-head variant
 constexpr int kFusedMaxK = 16;
-int g_fused_chunks = 0;        // 0 = choose per launch
-int g_fused_patches = 1;
 
 struct FusedPlan {
   int64_t M;
@@ -202,13 +295,14 @@ int check_fused(const gto_config *c, const void *hidden, int hidden_dim, const v
 
 // Rows are processed in blocks of 256; the vocabulary (tiles of 256 tokens) is split into chunks
 // so that there are at least ~8 workgroups per compute unit.
-FusedPlan fused_plan(int64_t M, int V, int ktop) {
+FusedPlan fused_plan(const gto_config *c, int64_t M, int ktop) {
+  const int V = c->V;
   FusedPlan p{};
   p.M = M;
   p.m_blocks = (int)((M + 255) / 256);
   p.n_tiles = (V + 255) / 256;
   // aim at ~14 workgroups per compute unit; a multiple of 8 chunks fills the per-XCD patches
-  int nc = g_fused_chunks > 0 ? g_fused_chunks : (((3584 + p.m_blocks - 1) / p.m_blocks + 7) / 8) * 8;
+  int nc = c->fused_chunks > 0 ? c->fused_chunks : (((3584 + p.m_blocks - 1) / p.m_blocks + 7) / 8) * 8;
   if (nc > 64) nc = 64;
   if (nc > p.n_tiles) nc = p.n_tiles;
   if (nc < 1) nc = 1;
@@ -232,8 +326,8 @@ struct FusedWs {
 FusedWs fused_ws(const gto_config *c) {
   FusedWs w{};
   const int64_t M = (int64_t)c->R * rows_per_root(c);
-  size_t b = fused_plan(M, c->V, c->k).bytes;
-  const size_t b1 = fused_plan(M, c->V, 1).bytes;
+  size_t b = fused_plan(c, M, c->k).bytes;
+  const size_t b1 = fused_plan(c, M, 1).bytes;
   w.partial_bytes = b1 > b ? b1 : b;
   const size_t n = (size_t)c->R * (size_t)(c->g > c->d ? c->g : c->d);
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -246,7 +340,7 @@ FusedWs fused_ws(const gto_config *c) {
   w.bytes = w.off_count + 256;
   // the backward pass lays the same memory out differently
   const size_t rd = (size_t)c->R * c->d;
-  const size_t bwd = fused_plan((int64_t)rd, c->V, 1).bytes + 2 * up(rd * sizeof(int32_t)) + 256;
+  const size_t bwd = fused_plan(c, (int64_t)rd, 1).bytes + 2 * up(rd * sizeof(int32_t)) + 256;
   if (bwd > w.bytes) w.bytes = bwd;
   return w;
 }
@@ -267,7 +361,7 @@ void run_gather(const gto_config *c, const gto_tree *t, const gto_reward *path, 
   pa.slot = reinterpret_cast<int64_t *>(base + L.off_slot);
   pa.tok = reinterpret_cast<int32_t *>(base + L.off_tok);
   gto::GatherDotArgs ga{};
-  ga.hidden = hidden; ga.w = w; ga.hidden_dim = hidden_dim;
+  ga.hidden = hidden; ga.w = w; ga.hidden_dim = hidden_dim; ga.V = c->V;
   ga.n = (int64_t)c->R * (mode == 0 ? c->g : c->d);
   ga.slot = pa.slot; ga.tok = pa.tok; ga.out = out;
   ProfScope ps(mode == 0 ? "gather_nodes" : "gather_path", st);
@@ -281,14 +375,14 @@ int run_fused_rows(const gto_config *c, const void *hidden, int hidden_dim, cons
                    int32_t *top_tok, float *top_logp, float *top_logit, void *ws, size_t ws_bytes,
                    const char *name, hipStream_t st) {
   const int64_t M = row_list ? n_list : (int64_t)c->R * rows_per_root(c);
-  const FusedPlan p = fused_plan(M, c->V, ktop);
+  const FusedPlan p = fused_plan(c, M, ktop);
   if (!ws || ws_bytes < p.bytes || (reinterpret_cast<uintptr_t>(ws) & 255)) return GTO_E_WORKSPACE;
   char *base = static_cast<char *>(ws);
   gto::FusedArgs a{};
   a.hidden = hidden; a.w = w; a.hidden_dim = hidden_dim; a.V = c->V; a.rho = rows_per_root(c); a.d = c->d;
   a.kslots = c->k; a.ktop = ktop; a.M = M; a.m_dev = n_dev; a.row_list = row_list; a.out_by_list = out_by_list;
   a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-  a.xcd_patches = g_fused_patches;
+  a.xcd_patches = c->fused_layout == 0;
   a.part_s = reinterpret_cast<double *>(base + p.off_s);
   a.part_m = reinterpret_cast<float *>(base + p.off_m);
   a.part_c = reinterpret_cast<float *>(base + p.off_c);
@@ -438,48 +532,19 @@ int gto_ppo_surrogate_fwd(const gto_config *cfg, const gto_tree *tree_cur, const
                           const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
                           const void *ref_logits_on_cur, const gto_draft_stats *ref_stats, const float *adv,
                           const gto_ppo *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  GTO_TRY(check_cfg(cfg, true));
-  GTO_TRY(check_logits(draft_logits_cur));
-  GTO_TRY(check_logits(ref_logits_on_cur));
-  GTO_TRY(check_tree(tree_cur));
-  GTO_TRY(check_reward(path_cur));
-  if (!draft_stats_cur || !draft_stats_cur->row_lse || !adv) return GTO_E_NULL;
-  GTO_TRY(check_ppo(out));
-  hipStream_t st = (hipStream_t)hip_stream;
-  const float *ref_lse = nullptr;
-  int by_step = 0;
+  GTO_TRY(check_ppo_fwd_args(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur, adv, out));
+  float *lse_by_step = nullptr;
   if (ref_stats) {
     if (!ref_stats->row_lse) return GTO_E_NULL;
-    ref_lse = ref_stats->row_lse;
   } else {
     size_t need = 0;
     GTO_TRY(gto_workspace_bytes(cfg, &need));
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255))
       return GTO_E_WORKSPACE;
-    gto::RowStatsArgs a{};
-    a.logits = ref_logits_on_cur;
-    a.row_stride = cfg->row_stride;
-    a.V = cfg->V; a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.rho = rows_per_root(cfg);
-    a.path_slot = path_cur->path_slot;
-    a.row_max = nullptr; a.row_lse = static_cast<float *>(workspace); a.top_tok = nullptr; a.top_logp = nullptr;
-    ProfScope ps("row_stats_ref_path", st);
-    gto::launch_row_stats(a, cfg->dtype, cfg->R * cfg->d, st);
-    ref_lse = static_cast<const float *>(workspace);
-    by_step = 1;
+    lse_by_step = static_cast<float *>(workspace);
   }
-  gto::PpoFwdArgs a{};
-  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.m = cfg->group_size; a.dtype = cfg->dtype;
-  a.row_stride = cfg->row_stride; a.eps = cfg->eps; a.grad_scale = cfg->grad_scale;
-  a.draft_logits = draft_logits_cur; a.ref_logits = ref_logits_on_cur;
-  a.draft_lse = draft_stats_cur->row_lse; a.ref_lse = ref_lse; a.ref_lse_by_step = by_step;
-  a.sel_tok = tree_cur->sel_tok; a.path_len = path_cur->path_len; a.path_node = path_cur->path_node;
-  a.path_slot = path_cur->path_slot; a.adv = adv;
-  a.logM = out->logM; a.logM0 = out->logM0; a.ratio = out->ratio; a.term = out->term; a.coef = out->coef;
-  a.loss_group = out->loss_group; a.loss = out->loss; a.active = out->active;
-  {
-    ProfScope ps("ppo_fwd", st);
-    gto::launch_ppo_fwd(a, st);
-  }
+  run_ppo_fwd(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur,
+              ref_stats ? ref_stats->row_lse : nullptr, lse_by_step, adv, out, (hipStream_t)hip_stream);
   return hip_status();
 }
 
@@ -580,7 +645,8 @@ int gto_tree_reward_fused(const gto_config *cfg, const gto_tree *tree, const voi
   run_gather(cfg, tree, nullptr, 0, hidden, hidden_dim, w_target_vh, workspace, L, node_logit, st);
   {
     gto::RewardArgs a{};
-    a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.dtype = cfg->dtype; a.reward_mode = cfg->reward_mode;
+    a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.V = cfg->V; a.dtype = cfg->dtype;
+    a.reward_mode = cfg->reward_mode;
     a.path_mode = cfg->path_mode;
     a.row_stride = 0; a.eta = cfg->eta;
     a.target_logits = nullptr; a.node_logit = node_logit; a.t_lse = stats_out->t_lse; a.t_argmax = stats_out->t_argmax;
@@ -616,7 +682,7 @@ int gto_ppo_surrogate_fwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
   run_gather(cfg, tree_cur, path_cur, 1, hidden_cur, hidden_dim, w_draft_vh, workspace, L, lc, st);
   run_gather(cfg, tree_cur, path_cur, 1, hidden_ref_on_cur, hidden_dim, w_draft_vh, workspace, L, lr, st);
   gto::PpoFwdArgs a{};
-  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.m = cfg->group_size; a.dtype = cfg->dtype;
+  a.R = cfg->R; a.d = cfg->d; a.k = cfg->k; a.g = cfg->g; a.m = cfg->group_size; a.dtype = cfg->dtype; a.V = cfg->V;
   a.row_stride = 0; a.eps = cfg->eps; a.grad_scale = cfg->grad_scale;
   a.draft_logits = nullptr; a.ref_logits = nullptr; a.path_logit_cur = lc; a.path_logit_ref = lr;
   a.draft_lse = draft_stats_cur->row_lse; a.ref_lse = ref_stats->row_lse; a.ref_lse_by_step = 0;
@@ -644,7 +710,7 @@ int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
   GTO_TRY(check_ws(workspace, workspace_bytes, fused_ws(cfg).bytes));
   hipStream_t st = (hipStream_t)hip_stream;
   const int64_t rd = (int64_t)cfg->R * cfg->d;
-  const FusedPlan p = fused_plan(rd, cfg->V, 1);
+  const FusedPlan p = fused_plan(cfg, rd, 1);
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   char *base = static_cast<char *>(workspace);
   int32_t *list_p = reinterpret_cast<int32_t *>(base + p.bytes);
@@ -663,7 +729,7 @@ int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
   a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
   a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
   a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-  a.xcd_patches = g_fused_patches;
+  a.xcd_patches = cfg->fused_layout == 0;
   a.part_s = reinterpret_cast<double *>(base + p.off_s);
   a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
   a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g; a.grad_rows = grad_rows;
@@ -745,12 +811,12 @@ int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_c
   }
   {
     // -coef * softmax of every path row, as two bf16 planes
-    const FusedPlan p = fused_plan(rd, cfg->V, 1);
+    const FusedPlan p = fused_plan(cfg, rd, 1);
     gto::FusedArgs a{};
     a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
     a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
     a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-    a.xcd_patches = g_fused_patches;
+    a.xcd_patches = cfg->fused_layout == 0;
     a.list_p = list_p; a.coef = fwd->coef; a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g;
     a.plane_hi = hi; a.plane_lo = lo; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node;
     a.part_s = reinterpret_cast<double *>(base + L.off_s);
@@ -764,19 +830,13 @@ int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_c
     a.m_blocks = L.m_blocks; a.h_blocks = L.h_blocks; a.n_splits = L.n_splits; a.slabs_per_split = L.slabs_per_split;
     a.partial = reinterpret_cast<float *>(base + L.off_partial);
     a.part_s = reinterpret_cast<const double *>(base + L.off_s);
-    a.n_chunks = fused_plan(rd, cfg->V, 1).n_chunks;
+    a.n_chunks = fused_plan(cfg, rd, 1).n_chunks;
     a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
     a.dh_rows = dh_rows;
     ProfScope ps("fused_dh", st);
     gto::launch_fused_dh(a, st);
   }
   return hip_status();
-}
-
-int gto_set_fused_tuning(int n_chunks, int xcd_patches) {
-  g_fused_chunks = n_chunks > 0 ? n_chunks : 0;
-  g_fused_patches = xcd_patches ? 1 : 0;
-  return GTO_OK;
 }
 
 int gto_token_loss_fwd(const gto_config *cfg, const void *draft_logits, const void *target_logits,
@@ -863,12 +923,12 @@ int gto_token_loss_fwd_fused(const gto_config *cfg, const void *hidden, int32_t 
   float *dl = reinterpret_cast<float *>(base + L.off_d), *tl = reinterpret_cast<float *>(base + L.off_t);
   for (int which = 0; which < 2; ++which) {
     // root rows only: with one used row per root, row i of the pass is slot (0,0) of root i
-    const FusedPlan p = fused_plan(cfg->R, cfg->V, 1);
+    const FusedPlan p = fused_plan(cfg, cfg->R, 1);
     gto::FusedArgs a{};
     a.hidden = hidden; a.w = which ? w_target_vh : w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = 1;
     a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = cfg->R;
     a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-    a.xcd_patches = g_fused_patches;
+    a.xcd_patches = cfg->fused_layout == 0;
     a.store_rows = which ? tl : dl; a.store_pitch = L.pitch;
     ProfScope ps(which ? "fused_root_logits_target" : "fused_root_logits_draft", st);
     gto::launch_fused_rows(a, st);
@@ -918,25 +978,20 @@ int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_str
   return hip_status();
 }
 
-int gto_set_waves_per_row(int waves) {
-  gto::set_waves_per_row(waves);
-  return gto::get_waves_per_row();
-}
-
 int gto_profile_enable(int on) {
-  t_prof_on = (on != 0);
+  if (on && t_prof.created == 0 && !t_prof.grow(kProfInitialPairs)) return hip_status();
+  t_prof.on = (on != 0);
   return GTO_OK;
 }
 
 int gto_profile_read(const char **names, int32_t *launches, double *total_ms, int cap) {
   if (!names || !launches || !total_ms || cap < 1) return GTO_E_NULL;
   int n = 0;
-  for (ProfRecord &rec : t_prof) {
+  for (ProfRecord &rec : t_prof.used) {
     (void)hipEventSynchronize(rec.stop);
     float ms = 0.f;
     (void)hipEventElapsedTime(&ms, rec.start, rec.stop);
-    (void)hipEventDestroy(rec.start);
-    (void)hipEventDestroy(rec.stop);
+    t_prof.free_pairs.emplace_back(rec.start, rec.stop);
     int slot = -1;
     for (int i = 0; i < n; ++i)
       if (strcmp(names[i], rec.name) == 0) slot = i;
@@ -950,7 +1005,7 @@ int gto_profile_read(const char **names, int32_t *launches, double *total_ms, in
     launches[slot] += 1;
     total_ms[slot] += (double)ms;
   }
-  t_prof.clear();
+  t_prof.used.clear();
   return n;
 }
 

@@ -472,6 +472,8 @@ __global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
   }
   if (a.top_tok == nullptr) return;
   const int total = nc * ktop;
+  __shared__ int s_claimed[FKT];
+  if (lane < FKT) s_claimed[lane] = 0;
   for (int j = lane; j < total; j += 64) {
     s_v[j] = a.part_v[g * total + j];
     s_i[j] = a.part_i[g * total + j];
@@ -484,10 +486,18 @@ __global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
     int rank = 0;
     for (int u = 0; u < total; ++u) rank += better(s_v[u], s_i[u], v, id) ? 1 : 0;
     if (rank < ktop) {
+      s_claimed[rank] = 1;
       a.top_tok[oi * ktop + rank] = id;
       if (a.top_logp) a.top_logp[oi * ktop + rank] = fminf((float)((double)v - lse), 0.f);
       if (a.top_logit) a.top_logit[oi * ktop + rank] = v;
     }
+  }
+  __syncthreads();
+  // ranks no entry claimed (possible only when the row held NaNs): a valid token id with probability zero
+  if (lane < ktop && s_claimed[lane] == 0) {
+    a.top_tok[oi * ktop + lane] = lane;
+    if (a.top_logp) a.top_logp[oi * ktop + lane] = neg_inf();
+    if (a.top_logit) a.top_logit[oi * ktop + lane] = neg_inf();
   }
 }
 
@@ -502,7 +512,7 @@ __global__ void k_fused_bwd_fixup(FusedArgs a) {
   const int pidx = a.list_p[g];
   const int rr = pidx / a.d;
   const int tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
-  a.grad_rows[(int64_t)pidx * a.V + tok] = (float)((double)a.coef[rr] * tot);
+  if (tok >= 0 && tok < a.V) a.grad_rows[(int64_t)pidx * a.V + tok] = (float)((double)a.coef[rr] * tot);
 }
 
 // Ordered compaction (single workgroup): the (root, step) pairs that carry a gradient, their
@@ -589,7 +599,7 @@ __global__ __launch_bounds__(64) void k_gather_dot(GatherDotArgs a) {
   const int lane = threadIdx.x;
   const int64_t slot = a.slot[p];
   const int tok = a.tok[p];
-  if (slot < 0 || tok < 0) {
+  if (slot < 0 || tok < 0 || tok >= a.V) {
     if (lane == 0) a.out[p] = 0.f;
     return;
   }
@@ -680,7 +690,7 @@ __global__ __launch_bounds__(256) void k_fused_dh_reduce(FusedDhArgs a) {
   if (g >= (int64_t)*a.m_dev) return;
   const int pidx = a.list_p[g];
   const int rr = pidx / a.d;
-  const int tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+  const int tok = min(max(a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]], 0), a.V - 1);
   const float coef = a.coef[rr];
   const uint16_t *wrow = static_cast<const uint16_t *>(a.w_vh) + (int64_t)tok * a.hidden_dim;
   double others = 0.0;                       // sum of the probabilities of all tokens but the accepted one

@@ -9,6 +9,7 @@ struct RowStatsArgs {
   const void *logits;
   int64_t row_stride;
   int V, d, kslots, ktop, rho;
+  int waves;                 // wavefronts per row: 0 = chosen per launch, else 1, 2, 4 or 8
   const int32_t *path_slot;  // null: all used slots; else rows (root, step) on an accepted path
   const int32_t *row_need;   // optional [R, d, kslots]: rows whose flag is 0 are skipped
   float *row_max;            // may be null
@@ -47,7 +48,7 @@ struct SelectArgs {
 };
 
 struct RewardArgs {
-  int R, d, k, g, dtype, reward_mode, path_mode;
+  int R, d, k, g, V, dtype, reward_mode, path_mode;
   int64_t row_stride;
   float eta;
   const void *target_logits;
@@ -68,7 +69,7 @@ struct AdvArgs {
 };
 
 struct PpoFwdArgs {
-  int R, d, k, g, m, dtype;
+  int R, d, k, g, m, dtype, V;
   int64_t row_stride;
   float eps, grad_scale;
   const void *draft_logits, *ref_logits;
@@ -138,7 +139,7 @@ struct BwdRowsArgs {
 
 struct GatherDotArgs {
   const void *hidden, *w;
-  int hidden_dim;
+  int hidden_dim, V;
   int64_t n;
   const int64_t *slot;       // [n] slot index of the hidden row, < 0: skip
   const int32_t *tok;        // [n]
@@ -175,8 +176,6 @@ struct TokenLossArgs {
   float *grad;                     // backward output [R, V]
 };
 void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t st);
-void set_waves_per_row(int w);
-int get_waves_per_row();
 void launch_row_stats(const RowStatsArgs &a, int dtype, int blocks, hipStream_t st);
 void launch_ppo_bwd(const PpoBwdArgs &a, int dtype, int blocks, hipStream_t st);
 void launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t st);

@@ -13,14 +13,9 @@
 #include "gto_device.h"
 #include "gto_kernels.h"
 
-#ifndef GTO_ROW_LOADS
-#define GTO_ROW_LOADS 4
-#endif
-#ifndef GTO_ROW_PREFETCH
-#define GTO_ROW_PREFETCH 0
-#endif
-
 namespace gto {
+
+constexpr int kRowLoads = 4;   // 16-byte loads in flight per lane and tile (2 and 8 measured about 1 % slower)
 
 // ----------------------------------------------------------------------------- top-k list
 // A wave keeps the 64 best (value, id) pairs it has seen, sorted, one per lane (lane 0 = best).
@@ -199,28 +194,11 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
   bool first = true;
 
   const int n_full = V / TILE;
-#if GTO_ROW_PREFETCH
-  // software pipeline: the loads of the next tile are in flight while this one is processed
-  if (wave < n_full) {
-    u32x4 qa[LOADS], qb[LOADS];
-    load_tile<T, LOADS, false>(row, wave * TILE, V, lane, qa);
-    for (int t = wave; t < n_full; t += WAVES) {
-      const bool more = (t + WAVES < n_full);
-      if (more) load_tile<T, LOADS, false>(row, (t + WAVES) * TILE, V, lane, qb);
-      scan_tile<T, LOADS, false, MODE>(qa, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
-      if (more) {
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) qa[u] = qb[u];
-      }
-    }
-  }
-#else
   for (int t = wave; t < n_full; t += WAVES) {
     u32x4 q[LOADS];
     load_tile<T, LOADS, false>(row, t * TILE, V, lane, q);
     scan_tile<T, LOADS, false, MODE>(q, t * TILE, V, lane, a.ktop, first, acc, top, thr_v, thr_i);
   }
-#endif
   if (n_full * TILE < V && (n_full % WAVES) == wave) {
     u32x4 q[LOADS];
     load_tile<T, LOADS, true>(row, n_full * TILE, V, lane, q);
@@ -269,6 +247,8 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
     a.row_lse[oi] = (float)lse;
   }
   if (MODE == kLseOnly || a.top_tok == nullptr) return;
+  __shared__ int sh_claimed[kWave];
+  if (threadIdx.x < kWave) sh_claimed[threadIdx.x] = 0;
   __syncthreads();
   // merge the WAVES sorted lists: rank each of the first ktop entries of every wave
   if (lane < a.ktop) {
@@ -278,10 +258,19 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
     for (int w = 0; w < WAVES; ++w)
       for (int i = 0; i < a.ktop; ++i) rank += better(sh_v[w * kWave + i], sh_i[w * kWave + i], v, id) ? 1 : 0;
     if (rank < a.ktop && id != kNoId) {
+      sh_claimed[rank] = 1;
       a.top_tok[oi * a.ktop + rank] = id;
       // clamped: rounding must never make a log-probability positive (a child may not outrank its parent)
       if (a.top_logp) a.top_logp[oi * a.ktop + rank] = fminf((float)((double)v - sh_lse), 0.f);
     }
+  }
+  __syncthreads();
+  // A row that holds NaNs can leave ranks unclaimed (a NaN wins no comparison).  Such a row's values are
+  // unspecified, but every id written must be a token of the vocabulary: unclaimed ranks get token `rank`
+  // (V >= ktop) with probability zero.
+  if (threadIdx.x < a.ktop && sh_claimed[threadIdx.x] == 0) {
+    a.top_tok[oi * a.ktop + threadIdx.x] = threadIdx.x;
+    if (a.top_logp) a.top_logp[oi * a.ktop + threadIdx.x] = neg_inf();
   }
 }
 
@@ -369,45 +358,80 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
 
 // ------------------------------------------------------------------------------- token-level loss
 // One workgroup per root: streams the root rows (slot (0,0)) of the draft and the target logits
-// together.  Forward: H = lse_M - sum_v p_T(v) d_v.  Backward: scale * (p_M - p_T) as an fp32 row.
-template <typename T, bool BWD>
-__global__ __launch_bounds__(256) void k_token_loss(TokenLossArgs a) {
+// together with 16-byte loads, two vectors of each row in flight per lane.  Forward:
+// H = lse_M - sum_v p_T(v) d_v.  Backward: scale * (p_M - p_T) as an fp32 row (16-byte stores when the
+// output rows are 16-byte aligned).  The last vector of a row may reach past V: it stays inside the
+// row's storage (row pitches are multiples of 16 bytes) and the surplus elements are masked.
+constexpr int kTokThreads = 256;
+template <typename T, bool BWD, bool VEC_ST>
+__global__ __launch_bounds__(kTokThreads) void k_token_loss(TokenLossArgs a) {
+  constexpr int EPV = Elem<T>::kPerVec;
   const int r = blockIdx.x;
   const float w = a.weight ? a.weight[r] : 1.f;
   const int64_t si = stat_index(r, 0, 0, a.d, a.k);
   const int64_t lo = a.root_stride ? (int64_t)r * a.root_stride : si * a.row_stride;
-  const T *__restrict__ drow = static_cast<const T *>(a.draft_logits) + lo;
-  const T *__restrict__ trow = static_cast<const T *>(a.target_logits) + lo;
+  const u32x4 *__restrict__ dvec = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.draft_logits) + lo);
+  const u32x4 *__restrict__ tvec = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.target_logits) + lo);
   const float d_lse = a.d_lse[si], t_lse = a.t_lse[si];
   const int V = a.V;
-  if (BWD) {
-    float *__restrict__ out = a.grad + (int64_t)r * V;
-    const float scale = a.grad_scale * w * a.inv_count[0];
-    for (int i = threadIdx.x; i < V; i += blockDim.x) {
-      const float pm = __builtin_amdgcn_exp2f((Elem<T>::load1(drow + i) - d_lse) * kLog2e);
-      const float pt = __builtin_amdgcn_exp2f((Elem<T>::load1(trow + i) - t_lse) * kLog2e);
-      out[i] = scale * (pm - pt);
-    }
-    return;
-  }
+  const int nvec = (V + EPV - 1) / EPV;
+  float *__restrict__ out = BWD ? a.grad + (int64_t)r * V : nullptr;
+  const float scale = BWD ? a.grad_scale * w * a.inv_count[0] : 0.f;
   double acc = 0.0;
-  for (int i0 = threadIdx.x * 8; i0 < V; i0 += blockDim.x * 8) {
-    float part = 0.f;
+  for (int i0 = threadIdx.x; i0 < nvec; i0 += 2 * kTokThreads) {
+    u32x4 qd[2], qt[2];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (i0 + e < V) {
-        const float tv = Elem<T>::load1(trow + i0 + e);
-        const float pt = __builtin_amdgcn_exp2f((tv - t_lse) * kLog2e);
-        const float dv = Elem<T>::load1(drow + i0 + e);
-        part += (pt > 0.f) ? pt * (dv - d_lse) : 0.f;      // 0 * log 0 := 0
+    for (int h = 0; h < 2; ++h) {
+      const int i = i0 + h * kTokThreads;
+      if (i < nvec) {
+        qd[h] = __builtin_nontemporal_load(dvec + i);
+        qt[h] = __builtin_nontemporal_load(tvec + i);
       }
     }
-    acc += (double)part;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int i = i0 + h * kTokThreads;
+      if (i >= nvec) continue;
+      float xd[EPV], xt[EPV];
+      Elem<T>::unpack(qd[h], xd);
+      Elem<T>::unpack(qt[h], xt);
+      if (BWD) {
+        float gq[EPV];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+          const float pm = __builtin_amdgcn_exp2f((xd[e] - d_lse) * kLog2e);
+          const float pt = __builtin_amdgcn_exp2f((xt[e] - t_lse) * kLog2e);
+          gq[e] = scale * (pm - pt);
+        }
+#pragma unroll
+        for (int q4 = 0; q4 < EPV / 4; ++q4) {
+          const int e0 = i * EPV + q4 * 4;
+          if (VEC_ST && e0 + 3 < V) {
+            const f32x4 o = {gq[q4 * 4], gq[q4 * 4 + 1], gq[q4 * 4 + 2], gq[q4 * 4 + 3]};
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out + e0));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (e0 + e < V) out[e0 + e] = gq[q4 * 4 + e];
+          }
+        }
+      } else {
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+          const float pt = __builtin_amdgcn_exp2f((xt[e] - t_lse) * kLog2e);
+          const float term = (pt > 0.f) ? pt * (xd[e] - d_lse) : 0.f;      // 0 * log 0 := 0
+          part += (i * EPV + e < V) ? term : 0.f;
+        }
+        acc += (double)part;
+      }
+    }
   }
-  __shared__ double s_red[256];
+  if (BWD) return;
+  __shared__ double s_red[kTokThreads];
   s_red[threadIdx.x] = acc;
   __syncthreads();
-  for (int off = 128; off >= 1; off >>= 1) {
+  for (int off = kTokThreads / 2; off >= 1; off >>= 1) {
     if ((int)threadIdx.x < off) s_red[threadIdx.x] += s_red[threadIdx.x + off];
     __syncthreads();
   }
@@ -440,13 +464,20 @@ __global__ __launch_bounds__(256) void k_token_loss_mean(TokenLossArgs a) {
 }
 
 void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t st) {
+  const dim3 grid(a.R), block(kTokThreads);
   if (bwd) {
-    if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, true>), dim3(a.R), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_token_loss<float, true>), dim3(a.R), dim3(256), 0, st, a);
+    const bool vec = (a.V % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.grad) & 15) == 0);
+    if (dtype == 0) {
+      if (vec) hipLaunchKernelGGL((k_token_loss<uint16_t, true, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((k_token_loss<uint16_t, true, false>), grid, block, 0, st, a);
+    } else {
+      if (vec) hipLaunchKernelGGL((k_token_loss<float, true, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((k_token_loss<float, true, false>), grid, block, 0, st, a);
+    }
     return;
   }
-  if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, false>), dim3(a.R), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((k_token_loss<float, false>), dim3(a.R), dim3(256), 0, st, a);
+  if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, false, false>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((k_token_loss<float, false, false>), grid, block, 0, st, a);
   hipLaunchKernelGGL(k_token_loss_mean, dim3(1), dim3(256), 0, st, a);
 }
 
@@ -464,14 +495,10 @@ void launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------- launchers
-static int g_waves_per_row = 0;   // 0 = choose per launch
-void set_waves_per_row(int w) { g_waves_per_row = (w == 1 || w == 2 || w == 4 || w == 8) ? w : 0; }
-int get_waves_per_row() { return g_waves_per_row; }
-
 // One wave per row streams best when rows are long and plentiful (one threshold, one list per
 // row).  With few rows, or short ones, split a row over more waves so the chip stays full.
-static int choose_waves(int V, int blocks, int elems_per_tile) {
-  if (g_waves_per_row) return g_waves_per_row;
+static int choose_waves(int forced, int V, int blocks, int elems_per_tile) {
+  if (forced) return forced;
   const int64_t wave_slots = 256 * 28;   // CUs x resident waves per CU at this kernel's register use
   int w = 1;
   while (w < 8 && (int64_t)blocks * w < wave_slots && V / (2 * w) >= 2 * elems_per_tile) w *= 2;
@@ -481,12 +508,12 @@ static int choose_waves(int V, int blocks, int elems_per_tile) {
 
 template <typename T, int MODE>
 static void launch_row_stats_m(const RowStatsArgs &a, int blocks, hipStream_t st) {
-  const int w = choose_waves(a.V, blocks, kWave * GTO_ROW_LOADS * Elem<T>::kPerVec);
+  const int w = choose_waves(a.waves, a.V, blocks, kWave * kRowLoads * Elem<T>::kPerVec);
   switch (w) {
-    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(64), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(128), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(512), 0, st, a); break;
-    default: hipLaunchKernelGGL((k_row_stats<T, 4, GTO_ROW_LOADS, MODE>), dim3(blocks), dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_row_stats<T, 1, kRowLoads, MODE>), dim3(blocks), dim3(64), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_row_stats<T, 2, kRowLoads, MODE>), dim3(blocks), dim3(128), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((k_row_stats<T, 8, kRowLoads, MODE>), dim3(blocks), dim3(512), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_row_stats<T, 4, kRowLoads, MODE>), dim3(blocks), dim3(256), 0, st, a); break;
   }
 }
 

@@ -123,7 +123,9 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
       const int p = a.cand_parent[pool0 + c];
       a.sel_cand[sel0 + i] = c;
       a.sel_tok[sel0 + i] = a.cand_tok[pool0 + c];
-      a.sel_parent[sel0 + i] = (p >= 0) ? s_rank[p] : -1;
+      // a parent always outranks its child (log-probabilities are <= 0); the range check only matters for
+      // rows that held NaNs, whose values are unspecified but whose indices must stay inside the list
+      a.sel_parent[sel0 + i] = (p >= 0 && s_rank[p] < i) ? s_rank[p] : -1;
       a.sel_depth[sel0 + i] = a.cand_depth[pool0 + c];
       a.sel_pslot[sel0 + i] = a.cand_pslot[pool0 + c];
       a.sel_slot[sel0 + i] = a.cand_slot[pool0 + c];
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
   for (int i = tid; i < n; i += kRewardThreads) {
     const int lvl = a.sel_depth[sel0 + i] - 1;
     const int js = a.sel_pslot[sel0 + i];
-    const int tok = a.sel_tok[sel0 + i];
+    const int tok = min(max(a.sel_tok[sel0 + i], 0), a.V - 1);     // ids come from the row kernels: always in range
     const int64_t si = stat_index(r, lvl, js, d, k);
     const float x = a.node_logit ? a.node_logit[sel0 + i] : Elem<T>::load1(logits + si * a.row_stride + tok);
     s_logt[i] = (double)x - (double)a.t_lse[si];
@@ -382,7 +384,7 @@ __global__ void k_ppo_root(PpoFwdArgs a) {
   for (int t = 0; t < l; ++t) {
     const int64_t rt = (int64_t)r * d + t;
     const int j = a.path_slot[rt];
-    const int tok = a.sel_tok[(int64_t)r * a.g + a.path_node[rt]];
+    const int tok = min(max(a.sel_tok[(int64_t)r * a.g + a.path_node[rt]], 0), a.V - 1);
     const int64_t si = stat_index(r, t, j, d, k);
     const float xc = a.path_logit_cur ? a.path_logit_cur[rt] : Elem<T>::load1(dl + si * a.row_stride + tok);
     lm += (double)xc - (double)a.draft_lse[si];

@@ -17,10 +17,11 @@ from . import binding as B
 class GtoPath:
     def __init__(self, *, R, d, k, g, V, dtype, group_size, device, row_stride=None, eta=1.0, eps=0.2,
                  delta=1e-6, grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, full_path=True,
-                 want_grad=True, path_mode=0):
+                 want_grad=True, path_mode=0, waves_per_row=0):
         self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=dtype, row_stride=row_stride,
                                  group_size=group_size, reward_mode=reward_mode, eta=eta, eps=eps,
-                                 delta=delta, grad_scale=grad_scale, flags=flags, path_mode=path_mode)
+                                 delta=delta, grad_scale=grad_scale, flags=flags, path_mode=path_mode,
+                                 waves_per_row=waves_per_row)
         self.device = device
         self.full_path = full_path
         self.want_grad = want_grad and full_path
@@ -71,10 +72,12 @@ class GtoFusedPath:
     (draft head for both draft models, target head for the target)."""
 
     def __init__(self, *, R, d, k, g, V, hidden, group_size, device, eta=1.0, eps=0.2, delta=1e-6,
-                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0, want_dh=False):
+                 grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0, want_dh=False,
+                 fused_chunks=0, fused_layout=0):
         self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=B.GTO_BF16, group_size=group_size,
                                  reward_mode=reward_mode, eta=eta, eps=eps, delta=delta, grad_scale=grad_scale,
-                                 flags=flags, path_mode=path_mode)
+                                 flags=flags, path_mode=path_mode, fused_chunks=fused_chunks,
+                                 fused_layout=fused_layout)
         self.hidden = hidden
         self.want_grad = want_grad
         self.buf = {}

@@ -7,6 +7,29 @@ from oracle import gto_oracle as O
 TAU = 1.0           # oracle's gap-to-error-budget ratio below which a ranking decision is a near tie
 
 
+def alloc_poisoned(alloc, cfg, device):
+    """Output buffers filled with a poison pattern instead of zeros: an entry the kernels should have
+    written but did not, or a read of one they never wrote, then shows up as a wild value."""
+    out = alloc(cfg, device)
+    for t in out.values():
+        if t.dtype == torch.int32:
+            t.fill_(0x7F7F7F7F)
+        else:
+            t.fill_(float("nan"))
+    return out
+
+
+def poison_path(path):
+    """Poison every output buffer of a GtoPath / GtoFusedPath (see alloc_poisoned)."""
+    for tag in path.buf:
+        for grp in path.buf[tag].values():
+            for t in grp.values():
+                t.fill_(0x7F7F7F7F if t.dtype == torch.int32 else float("nan"))
+    for t in path.ppo.values():
+        t.fill_(0x7F7F7F7F if t.dtype == torch.int32 else float("nan"))
+    path.adv.fill_(float("nan"))
+
+
 def to_np(d):
     return {k: v.detach().cpu().numpy() for k, v in d.items() if v is not None}
 

@@ -40,9 +40,10 @@ def _oracle_logits(t, roots):
     return out
 
 
-def _run(w, t, device, flags=0):
+def _run(w, t, device, flags=0, fused_chunks=0, fused_layout=0):
     path = GtoFusedPath(R=t["H_cur"].shape[0], d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m,
-                        device=device, eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags)
+                        device=device, eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags,
+                        fused_chunks=fused_chunks, fused_layout=fused_layout)
     if flags == 0:
         path.grad_rows.fill_(7.0)
     path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"])
@@ -152,16 +153,12 @@ def test_fused_row_statistics_when_the_maximum_moves_far(gpu_device, nc):
     W = b[:, None].expand(V, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
     scale = torch.tensor([1.0, -1.0, 0.5, -0.5, 2.0, 0.25])
     H = scale[:, None, None, None].expand(R, d, k, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
-    cfg = G.make_config(R=R, d=d, k=k, g=4, V=V, dtype=torch.bfloat16)
+    cfg = G.make_config(R=R, d=d, k=k, g=4, V=V, dtype=torch.bfloat16, fused_chunks=nc)
     ws = torch.empty(G.gto_fused_workspace_bytes(cfg, hidden), dtype=torch.uint8, device=gpu_device)
     ds, ts = G.alloc_draft_stats(cfg, gpu_device), G.alloc_target_stats(cfg, gpu_device)
-    try:
-        G.gto_set_fused_tuning(nc, True)
-        G.gto_fused_draft_row_stats(cfg, H, W, ds, ws)
-        G.gto_fused_target_row_stats(cfg, H, W, ts, ws)
-        torch.cuda.synchronize()
-    finally:
-        G.gto_set_fused_tuning(0, True)
+    G.gto_fused_draft_row_stats(cfg, H, W, ds, ws)
+    G.gto_fused_target_row_stats(cfg, H, W, ts, ws)
+    torch.cuda.synchronize()
     L = O.fused_logits(H.float().cpu().numpy(), W.float().cpu().numpy())
     od, ot = O.draft_row_stats(L, k), O.target_row_stats(L)
     gd, gt = U.to_np(ds), U.to_np(ts)
@@ -297,21 +294,17 @@ def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
                         w_corr=0.9, ref_sigma=0.05)
     t = S.make_fused(w, gpu_device)
-    try:
-        ref = _run(w, t, gpu_device)
-        for nc, patches in ((1, False), (3, True), (16, True)):
-            G.gto_set_fused_tuning(nc, patches)
-            other = _run(w, t, gpu_device)
-            for tag in ("cur", "ref"):
-                for grp in ("tree", "reward"):
-                    for n, x in ref.buf[tag][grp].items():
-                        if x.dtype == torch.int32:
-                            assert torch.equal(x, other.buf[tag][grp][n]), (nc, tag, grp, n)
-            assert torch.equal(ref.grad_slot, other.grad_slot)
-            v = ref.grad_slot >= 0
-            torch.testing.assert_close(ref.grad_rows[v], other.grad_rows[v], rtol=1e-5, atol=1e-9)
-    finally:
-        G.gto_set_fused_tuning(0, True)
+    ref = _run(w, t, gpu_device)
+    for nc, layout in ((1, 1), (3, 0), (16, 0)):
+        other = _run(w, t, gpu_device, fused_chunks=nc, fused_layout=layout)
+        for tag in ("cur", "ref"):
+            for grp in ("tree", "reward"):
+                for n, x in ref.buf[tag][grp].items():
+                    if x.dtype == torch.int32:
+                        assert torch.equal(x, other.buf[tag][grp][n]), (nc, tag, grp, n)
+        assert torch.equal(ref.grad_slot, other.grad_slot)
+        v = ref.grad_slot >= 0
+        torch.testing.assert_close(ref.grad_rows[v], other.grad_rows[v], rtol=1e-5, atol=1e-9)
 
 
 def test_fused_target_pruning_changes_nothing_but_the_rows_multiplied(gpu_device):

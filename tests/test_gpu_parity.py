@@ -135,29 +135,25 @@ def _compare_ppo(w, tens, path, ora_unused=None, grad_scale=0.5, reward_key="rew
                                             ("f32", 9000, 9000)])
 def test_row_kernels_match_oracle(gpu_device, dtype, V, stride, waves):
     _say(f"row kernels dtype={dtype} V={V} stride={stride} waves={waves}")
-    G.gto_set_waves_per_row(waves)
-    try:
-        R, d, k = 5, 3, 10
-        w = S.scaled(S.CONFIGS["llama31_8b"], R=R, V=stride, d=d, k=k, g=20, dtype=dtype, n_peaks=8)
-        tens = S.make_logits(w, gpu_device, want=("D_cur", "T_cur"))
-        D, T = tens["D_cur"], tens["T_cur"]
-        D[0, 1, 2, 5:V:7] = float("-inf")                  # zero-probability tokens
-        D[1, 0, 0, :] = 1.5                                # a flat row: pure id tie-break
-        T[1, 1, 1, :] = -2.0
-        T[2, 2, 3, V - 1] = 40.0                           # argmax in the ragged tail
-        D[2, 2, 1, V - 3:V] = 30.0                         # top entries in the ragged tail, tied
-        if stride > V:
-            D[..., V:] = 99.0                              # padding must never be read as data
-            T[..., V:] = 99.0
-        cfg = G.make_config(R=R, d=d, k=k, g=20, V=V, dtype=w.torch_dtype, row_stride=stride)
-        ds = G.gto_draft_row_stats(cfg, D, G.alloc_draft_stats(cfg, gpu_device))
-        ts = G.gto_target_row_stats(cfg, T, G.alloc_target_stats(cfg, gpu_device))
-        torch.cuda.synchronize()
-        Dn, Tn = U.logits_np(D)[..., :V], U.logits_np(T)[..., :V]
-        U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
-        U.check_target_stats(U.to_np(ts), O.target_row_stats(Tn))
-    finally:
-        G.gto_set_waves_per_row(0)
+    R, d, k = 5, 3, 10
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=R, V=stride, d=d, k=k, g=20, dtype=dtype, n_peaks=8)
+    tens = S.make_logits(w, gpu_device, want=("D_cur", "T_cur"))
+    D, T = tens["D_cur"], tens["T_cur"]
+    D[0, 1, 2, 5:V:7] = float("-inf")                  # zero-probability tokens
+    D[1, 0, 0, :] = 1.5                                # a flat row: pure id tie-break
+    T[1, 1, 1, :] = -2.0
+    T[2, 2, 3, V - 1] = 40.0                           # argmax in the ragged tail
+    D[2, 2, 1, V - 3:V] = 30.0                         # top entries in the ragged tail, tied
+    if stride > V:
+        D[..., V:] = 99.0                              # padding must never be read as data
+        T[..., V:] = 99.0
+    cfg = G.make_config(R=R, d=d, k=k, g=20, V=V, dtype=w.torch_dtype, row_stride=stride, waves_per_row=waves)
+    ds = G.gto_draft_row_stats(cfg, D, U.alloc_poisoned(G.alloc_draft_stats, cfg, gpu_device))
+    ts = G.gto_target_row_stats(cfg, T, U.alloc_poisoned(G.alloc_target_stats, cfg, gpu_device))
+    torch.cuda.synchronize()
+    Dn, Tn = U.logits_np(D)[..., :V], U.logits_np(T)[..., :V]
+    U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
+    U.check_target_stats(U.to_np(ts), O.target_row_stats(Tn))
 
 
 def test_rows_with_fewer_than_k_finite_logits(gpu_device):
@@ -171,6 +167,61 @@ def test_rows_with_fewer_than_k_finite_logits(gpu_device):
     torch.cuda.synchronize()
     Dn = U.logits_np(D)
     U.check_row_stats(U.to_np(ds), O.draft_row_stats(Dn, k), Dn, k)
+
+
+def test_nan_rows_give_no_fault_and_leave_other_roots_alone(gpu_device):
+    """The header's contract for a row that holds NaNs: unspecified values for that root, but every
+    index written stays in range, the call completes, and roots of other groups are untouched.  Output
+    buffers are poisoned first, so an entry that a kernel forgot to write shows up as a wild index."""
+    _say("NaN rows: no fault, indices in range, other roots unchanged")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=9000, m=4)
+    tens = S.make_logits(w, gpu_device)
+    good = _run_full(w, tens, gpu_device)
+    bad = {n: t.clone() for n, t in tens.items()}
+    bad["D_cur"][1, 1, 2, :] = float("nan")            # a whole draft row
+    bad["D_cur"][1, 0, 0, 100:4000] = float("nan")     # most of a root row
+    bad["T_cur"][2, 1, 0, :] = float("nan")            # a whole target row
+    bad["T_cur"][2, 0, 0, 17] = float("nan")           # a single entry
+    bad["D_ref"][6, 2, 1, :] = float("nan")
+    bad["T_ref"][6, 0, 0, :] = float("nan")
+    for flags in (0, G.GTO_FLAG_TARGET_PRUNE):
+        path = GtoPath(R=16, d=w.d, k=w.k, g=w.g, V=w.V, dtype=w.torch_dtype, group_size=w.m, device=gpu_device,
+                       eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags)
+        U.poison_path(path)
+        path.grad_rows.fill_(7.0)
+        path.step(bad["D_cur"], bad["T_cur"], bad["D_ref"], bad["T_ref"])
+        torch.cuda.synchronize()                       # completes: no fault, no hang
+        used = torch.from_numpy(U.used_mask(16, w.d, w.k)).to(gpu_device)
+        for tag in ("cur", "ref"):
+            b = path.buf[tag]
+            tt = b["dstats"]["top_tok"][used]
+            assert bool(((tt >= 0) & (tt < w.V)).all()), tag
+            tr, rw = b["tree"], b["reward"]
+            assert bool((tr["n_sel"] == min(w.g, w.C)).all())
+            assert bool(((tr["sel_tok"] >= 0) & (tr["sel_tok"] < w.V)).all())
+            idx = torch.arange(w.g, device=gpu_device)[None, :]
+            assert bool(((tr["sel_parent"] >= -1) & (tr["sel_parent"] < idx)).all())
+            assert bool(((tr["sel_pslot"] >= 0) & (tr["sel_pslot"] < w.k)).all())
+            assert bool(((tr["sel_slot"] >= -1) & (tr["sel_slot"] < w.k)).all())
+            assert bool(((rw["path_len"] >= 0) & (rw["path_len"] <= w.d)).all())
+            assert bool(((rw["path_node"] >= -1) & (rw["path_node"] < w.g)).all())
+            assert bool(((rw["path_slot"] >= -1) & (rw["path_slot"] < w.k)).all())
+            need = tr["slot_need"].bool() if flags else used
+            ta = b["tstats"]["t_argmax"][need & used]
+            assert bool(((ta >= 0) & (ta < w.V)).all()), tag
+        assert bool(((path.grad_slot >= -1) & (path.grad_slot < w.k)).all())
+        # roots 8..15 (groups 2 and 3) saw no NaN: identical to the clean run, bit for bit
+        clean = slice(8, 16)
+        for tag in ("cur", "ref"):
+            for grp in ("pool", "tree", "reward"):
+                for n, x in good.buf[tag][grp].items():
+                    assert torch.equal(x[clean], path.buf[tag][grp][n][clean]), (flags, tag, grp, n)
+        for n in ("logM", "logM0", "ratio", "term", "active"):
+            assert torch.equal(good.ppo[n][clean], path.ppo[n][clean]), (flags, n)
+        assert torch.equal(good.ppo["loss_group"][2:], path.ppo["loss_group"][2:])
+        assert torch.equal(good.adv[clean], path.adv[clean])
+        assert torch.equal(good.grad_slot[clean], path.grad_slot[clean])
+        assert torch.equal(good.grad_rows[clean], path.grad_rows[clean])
 
 
 # ------------------------------------------------------------------------------------ full path

@@ -61,25 +61,21 @@ def test_random_shapes_streaming(gpu_device, seed):
 
 def test_random_shapes_fused(gpu_device):
     rng = random.Random(1)
-    try:
-        for it in range(10):
-            k = rng.choice([1, 2, 4, 5, 8, 10, 16])
-            d = rng.choice([1, 2, 3, 4])
-            C = k + (d - 1) * k * k
-            g = rng.choice([1, max(1, C // 3), C, C + 2, 20])
-            m = rng.choice([1, 2, 8])
-            R = m * rng.choice([1, 2, 5])
-            hidden = rng.choice([64, 128, 192, 256, 448])
-            V = max(((k + 7) // 8) * 8, rng.choice([8, 64, 200, 256, 1032, 2048, 3000, 4104]))
-            corr = rng.choice([0.0, 0.8, 0.95])
-            w = S.FusedWorkload(f"rnd{it}", R=R, V=V, k=k, d=d, g=g, m=m, hidden=hidden, h_scale=3.0, w_sigma=0.05,
-                                w_corr=corr, ref_sigma=0.05, seed=5000 + it)
-            nc = rng.choice([0, 1, 3])
-            T._say(f"random fused shape {it}: R={R} d={d} k={k} g={g} m={m} hidden={hidden} V={V} corr={corr} chunks={nc}")
-            t = S.make_fused(w, gpu_device)
-            G.gto_set_fused_tuning(nc, True)
-            path = F._run(w, t, gpu_device)
-            L, _ = F._compare_fused(w, t, path, list(range(R)))
-            T._compare_ppo(w, L, path)
-    finally:
-        G.gto_set_fused_tuning(0, True)
+    for it in range(10):
+        k = rng.choice([1, 2, 4, 5, 8, 10, 16])
+        d = rng.choice([1, 2, 3, 4])
+        C = k + (d - 1) * k * k
+        g = rng.choice([1, max(1, C // 3), C, C + 2, 20])
+        m = rng.choice([1, 2, 8])
+        R = m * rng.choice([1, 2, 5])
+        hidden = rng.choice([64, 128, 192, 256, 448])
+        V = max(((k + 7) // 8) * 8, rng.choice([8, 64, 200, 256, 1032, 2048, 3000, 4104]))
+        corr = rng.choice([0.0, 0.8, 0.95])
+        w = S.FusedWorkload(f"rnd{it}", R=R, V=V, k=k, d=d, g=g, m=m, hidden=hidden, h_scale=3.0, w_sigma=0.05,
+                            w_corr=corr, ref_sigma=0.05, seed=5000 + it)
+        nc = rng.choice([0, 1, 3])
+        T._say(f"random fused shape {it}: R={R} d={d} k={k} g={g} m={m} hidden={hidden} V={V} corr={corr} chunks={nc}")
+        t = S.make_fused(w, gpu_device)
+        path = F._run(w, t, gpu_device, fused_chunks=nc)
+        L, _ = F._compare_fused(w, t, path, list(range(R)))
+        T._compare_ppo(w, L, path)

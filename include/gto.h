@@ -229,6 +229,23 @@ int gto_ppo_surrogate_fwd(const gto_config *cfg, const gto_tree *tree_cur,
                           const gto_ppo *out, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
 
+/* gto_ppo_surrogate_fwd for callers that cannot allocate device memory and therefore have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same outputs as gto_ppo_surrogate_fwd called with ref_stats == NULL (the reference
+ * rows' log-sum-exps are recomputed for the rows on the accepted paths), bit for bit; the [R, d]
+ * floats of scratch memory live in a static device array inside the library (256 KiB, held by every
+ * GPU the library runs on until the process ends).  The call allocates nothing and frees nothing.
+ *   - Limit: R * d <= 65536, else GTO_E_WORKSPACE (nothing is launched).
+ *   - The first call on a device looks up the array's address on that device (a host-side query, no
+ *     allocation); make one call on each device before recording calls into a graph.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents.  Nothing
+ *     in it has to start at zero: each call writes every entry it later reads.  Two calls that
+ *     overlap in time on one GPU (different streams without ordering) race on it: order them. */
+int gto_ppo_surrogate_fwd_noalloc(const gto_config *cfg, const gto_tree *tree_cur,
+                                  const gto_reward *path_cur, const void *draft_logits_cur,
+                                  const gto_draft_stats *draft_stats_cur, const void *ref_logits_on_cur,
+                                  const float *adv, const gto_ppo *out, void *hip_stream);
+
 /* Gradient of cfg->grad_scale * loss w.r.t. the current draft logits (derivative of Eq. 11-12
  * with the advantage and the tree held constant): for step t < l_i of root i,
  *   grad_rows[i, t, v] = coef_i * (1[v == token_t] - softmax(row)[v]),

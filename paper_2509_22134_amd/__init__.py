@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     gto_version, gto_strerror, gto_workspace_bytes,
     gto_draft_row_stats, gto_target_row_stats, gto_expand_tree, gto_expand_from_stats,
     gto_select_topg, gto_tree_reward, gto_reward_from_stats, gto_group_advantage,
-    gto_ppo_surrogate_fwd, gto_ppo_surrogate_bwd, gto_calibration_copy, gto_token_loss_fwd, gto_token_loss_bwd,
+    gto_ppo_surrogate_fwd, gto_ppo_surrogate_bwd, gto_ppo_surrogate_fwd_noalloc, gto_calibration_copy, gto_token_loss_fwd, gto_token_loss_bwd,
     gto_fused_workspace_bytes, gto_fused_draft_row_stats, gto_fused_target_row_stats,
     gto_expand_tree_fused, gto_tree_reward_fused, gto_ppo_surrogate_fwd_fused, gto_ppo_surrogate_bwd_fused,
     gto_fused_dh_workspace_bytes, gto_ppo_surrogate_bwd_fused_dh, gto_fused_token_loss_workspace_bytes,

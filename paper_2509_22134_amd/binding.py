@@ -90,6 +90,8 @@ def lib():
     L.gto_group_advantage.argtypes = [cfgp, VP, VP, VP, VP]
     L.gto_ppo_surrogate_fwd.argtypes = [cfgp, P(gto_tree), P(gto_reward), VP, P(gto_draft_stats), VP,
                                         P(gto_draft_stats), VP, P(gto_ppo), VP, SZ, VP]
+    L.gto_ppo_surrogate_fwd_noalloc.argtypes = [cfgp, P(gto_tree), P(gto_reward), VP, P(gto_draft_stats), VP, VP,
+                                                P(gto_ppo), VP]
     L.gto_ppo_surrogate_bwd.argtypes = [cfgp, P(gto_tree), P(gto_reward), P(gto_ppo), VP, P(gto_draft_stats),
                                         VP, VP, VP]
     L.gto_calibration_copy.argtypes = [VP, VP, SZ, VP]
@@ -118,6 +120,7 @@ def lib():
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
+                 "gto_ppo_surrogate_fwd_noalloc",
                  "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
                  "gto_expand_tree_fused", "gto_tree_reward_fused",
@@ -292,6 +295,16 @@ def gto_ppo_surrogate_fwd(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats
     _check(lib().gto_ppo_surrogate_fwd(C.byref(cfg), _ref(t), _ref(w), _dp(draft_logits_cur), _ref(ds),
                                        _dp(ref_logits_on_cur), _ref(rs), _dp(adv), _ref(o), ws, wb, _stream(stream)),
            "gto_ppo_surrogate_fwd")
+    return out
+
+
+def gto_ppo_surrogate_fwd_noalloc(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur,
+                                  adv, out, stream=None):
+    t, w = _pack(gto_tree, _TREE, tree_cur), _pack(gto_reward, _REWARD, path_cur)
+    ds, o = _pack(gto_draft_stats, _DRAFT, draft_stats_cur), _pack(gto_ppo, _PPO, out)
+    _check(lib().gto_ppo_surrogate_fwd_noalloc(C.byref(cfg), _ref(t), _ref(w), _dp(draft_logits_cur), _ref(ds),
+                                               _dp(ref_logits_on_cur), _dp(adv), _ref(o), _stream(stream)),
+           "gto_ppo_surrogate_fwd_noalloc")
     return out
 
 

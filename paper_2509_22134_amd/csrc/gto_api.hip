@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -70,6 +71,42 @@ struct ProfScope {
     t_prof.used.push_back(rec);
   }
 };
+
+// ------------------------------------------------------------------------- static scratch
+// Scratch memory of gto_ppo_surrogate_fwd_noalloc: the log-sum-exp of the reference model's rows on the
+// accepted paths, [R, d] floats.  Every GPU the library runs on holds its own copy of this array at its
+// own address until the process ends; host code must only ever use the per-device address obtained from
+// hipGetSymbolAddress below, never the array's name.
+constexpr int kNoAllocMaxRows = 65536;                    // R * d of one call; 256 KiB per GPU
+static __device__ __align__(256) float scratch[kNoAllocMaxRows];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};                   // written once per device, under the mutex
+
+// Address of `scratch` on the current device (resolved on the first call on that device).
+int scratch_on_current_device(float **out) {
+  int dev = -1;
+  const hipError_t ed = hipGetDevice(&dev);
+  if (ed != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    t_hip_error = std::string("HIP error: ") + (ed != hipSuccess ? hipGetErrorString(ed) : "device ordinal out of range");
+    (void)hipGetLastError();
+    return GTO_E_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      t_hip_error = std::string("HIP error: ") + hipGetErrorString(e);
+      (void)hipGetLastError();
+      return GTO_E_HIP;
+    }
+    g_scratch_ptr[dev] = static_cast<float *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return GTO_OK;
+}
 
 // ------------------------------------------------------------------------- validation
 constexpr int kMaxK = 64, kMaxD = 32, kMaxPool = 4096;
@@ -414,7 +451,7 @@ const char *gto_strerror(int status) {
     case GTO_E_ALIGN: return "logits base or row stride is not 16-byte aligned";
     case GTO_E_DTYPE: return "unknown logits dtype";
     case GTO_E_MODE: return "unknown reward mode or unusable eta/eps/delta";
-    case GTO_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GTO_E_WORKSPACE: return "workspace missing, misaligned or too small (for a no-alloc call: size beyond the static scratch array)";
     case GTO_E_HIP: return t_hip_error.empty() ? "HIP error" : t_hip_error.c_str();
     default: return "unknown status";
   }
@@ -545,6 +582,21 @@ int gto_ppo_surrogate_fwd(const gto_config *cfg, const gto_tree *tree_cur, const
   }
   run_ppo_fwd(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur,
               ref_stats ? ref_stats->row_lse : nullptr, lse_by_step, adv, out, (hipStream_t)hip_stream);
+  return hip_status();
+}
+
+int gto_ppo_surrogate_fwd_noalloc(const gto_config *cfg, const gto_tree *tree_cur, const gto_reward *path_cur,
+                                  const void *draft_logits_cur, const gto_draft_stats *draft_stats_cur,
+                                  const void *ref_logits_on_cur, const float *adv, const gto_ppo *out,
+                                  void *hip_stream) {
+  GTO_TRY(check_ppo_fwd_args(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur, adv, out));
+  if ((int64_t)cfg->R * cfg->d > kNoAllocMaxRows) return GTO_E_WORKSPACE;
+  float *lse_by_step = nullptr;
+  GTO_TRY(scratch_on_current_device(&lse_by_step));
+  // nothing in the scratch needs clearing: the row pass writes the entry of every (root, step) on an
+  // accepted path before the surrogate kernel reads exactly those entries, on the same stream
+  run_ppo_fwd(cfg, tree_cur, path_cur, draft_logits_cur, draft_stats_cur, ref_logits_on_cur, nullptr, lse_by_step,
+              adv, out, (hipStream_t)hip_stream);
   return hip_status();
 }
 

@@ -263,6 +263,11 @@ class FusedWorkload:
 
 FUSED_CONFIGS: Dict[str, FusedWorkload] = {
     "llama33_70b_fused": FusedWorkload("llama33_70b_fused", R=1024, V=128256, k=8, d=8, g=80, m=8, hidden=8192),
+    # the same shape with a target head correlated with the draft head, so that target and draft agree often
+    # enough for accepted paths (and hence a backward with real rows) to exist; not one of the five named
+    # configurations (whose second head is an independent draw), a companion that exercises the gradient
+    "llama33_70b_fused_corr": FusedWorkload("llama33_70b_fused_corr", R=1024, V=128256, k=8, d=8, g=80, m=8,
+                                            hidden=8192, w_corr=0.95),
 }
 
 

@@ -12,6 +12,27 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_collection_finish(session):
+    """The full-size parity tests fan the oracle out over CPU-only worker processes.  They are forked here,
+    once collection is done and before any test (or fixture) makes the process's first GPU call; counting
+    devices does not initialise the GPU."""
+    if not any(item.get_closest_marker("gpu") for item in session.items):
+        return
+    try:
+        import torch
+        if torch.cuda.device_count() < 1:
+            return
+    except Exception:
+        return
+    import oracle_pool
+    oracle_pool.start()
+
+
+def pytest_sessionfinish(session, exitstatus):
+    import oracle_pool
+    oracle_pool.stop()
+
+
 def has_gpu() -> bool:
     try:
         import torch
@@ -26,3 +47,11 @@ def gpu_device():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="session")
+def oracle_workers(gpu_device):
+    import oracle_pool
+    if not oracle_pool.started():
+        pytest.skip("oracle workers were not started (no GPU test was collected)")
+    return oracle_pool

@@ -20,11 +20,7 @@ from test_gpu_parity import _compare_ppo, _say
 pytestmark = pytest.mark.gpu
 
 
-def logit_error_bound(hidden, max_abs_logit):
-    """Absolute error granted to an fp32-accumulated logit: 2^-21 per unit of the largest |logit|
-    (a few fp32 roundings of the running sum), growing like the square root of the number of
-    accumulation steps beyond 1024."""
-    return 2.0 ** -21 * max_abs_logit * max(1.0, (hidden / 1024.0) ** 0.5)
+logit_error_bound = U.logit_error_bound
 
 
 def _oracle_logits(t, roots):
@@ -53,41 +49,7 @@ def _run(w, t, device, flags=0, fused_chunks=0, fused_layout=0):
 
 def _compare_fused(w, t, path, roots):
     L = _oracle_logits(t, roots)
-    E = logit_error_bound(w.hidden, max(float(np.abs(v).max()) for v in L.values()))
-    rtol = max(1e-5, 4 * w.d * E)
-    ora = O.full_path(L["D_cur"], L["T_cur"], L["D_ref"], L["T_ref"], k=w.k, d=w.d, g=w.g, m=1, eta=w.eta,
-                      eps=w.eps, delta=w.delta, want_grad=False, logit_err=E)
-    n_ambig = 0
-    m = U.used_mask(len(roots), w.d, w.k)
-    for tag in ("cur", "ref"):
-        b = path.buf[tag]
-        gd = {k: v[roots] for k, v in U.to_np(b["dstats"]).items()}
-        gt = {k: v[roots] for k, v in U.to_np(b["tstats"]).items()}
-        gpool = {k: v[roots] for k, v in U.to_np(b["pool"]).items()}
-        gtree = {k: v[roots] for k, v in U.to_np(b["tree"]).items()}
-        grew = {k: v[roots] for k, v in U.to_np(b["reward"]).items()}
-        o, Dn, Tn = ora[tag], L["D_" + tag], L["T_" + tag]
-        # stage 1: the GPU's logits at its own top tokens are the oracle's within E; statistics within E
-        g_logit = gd["top_logp"].astype(np.float64) + gd["row_lse"].astype(np.float64)[..., None]
-        o_at = np.take_along_axis(Dn, gd["top_tok"].astype(np.int64).clip(0, w.V - 1), axis=-1)
-        assert np.abs(g_logit - o_at)[m].max() <= E + 4e-6, float(np.abs(g_logit - o_at)[m].max())
-        assert np.abs(gd["row_lse"] - o["dstats"]["row_lse"])[m].max() <= E + 2e-6
-        assert np.abs(gt["t_lse"] - o["tstats"]["t_lse"])[m].max() <= E + 2e-6
-        assert np.abs(gd["row_max"] - o["dstats"]["row_max"])[m].max() <= E
-        rm_d, rm_t = O.row_margins(Dn, w.k, E), O.row_margins(Tn, 1, E)
-        clear_rows = (rm_d >= 1.0) & (rm_t >= 1.0)
-        for r in np.nonzero(clear_rows)[0]:
-            assert np.array_equal(gd["top_tok"][r][m[r]], o["dstats"]["top_tok"][r][m[r]]), (tag, r)
-            assert np.array_equal(gt["t_argmax"][r][m[r]], o["tstats"]["t_argmax"][r][m[r]]), (tag, r)
-        # stage 2: oracle logic on the GPU's own statistics, bit for bit
-        pool2, tree2, rew2, path2 = U.oracle_from_gpu_stats(gd, gt, Tn, w.d, w.k, w.g, w.eta)
-        U.check_stage2(gpool, gtree, grew, pool2, tree2, rew2, path2, rtol=rtol)
-        # stage 3: end to end where every decision is clear of the logit error
-        margin = np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"])
-        clear = np.nonzero((margin >= 1.0) & clear_rows)[0]
-        n_ambig += len(roots) - len(clear)
-        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear,
-                       exact_scores=False, rtol=rtol, score_atol=4e-6 + 2 * w.d * E)
+    _, _, n_ambig, _, _ = U.compare_trees_fused(w, L, U.bundle_np(path, roots, with_ppo=False))
     return L, n_ambig
 
 
@@ -340,57 +302,3 @@ def test_fused_zero_fill(gpu_device):
     v = a.grad_slot >= 0
     assert torch.equal(a.grad_slot, b.grad_slot) and torch.equal(a.grad_rows[v], b.grad_rows[v])
     assert not b.grad_rows[~v].any() and bool((a.grad_rows[~v] == 7.0).all())
-
-
-def test_fused_full_size_config_sampled_roots(gpu_device):
-    """The fifth configuration at its real shape, in the launch configuration bench.py times; the
-    oracle (one fp64 matmul per root and tensor) checks sampled roots."""
-    w = S.FUSED_CONFIGS["llama33_70b_fused"]
-    _say(f"full size {w.name}: R={w.R} V={w.V} k={w.k} d={w.d} g={w.g} hidden={w.hidden}")
-    t = S.make_fused(w, gpu_device)
-    _say("  inputs generated")
-    path = _run(w, t, gpu_device)
-    _say("  GPU path done")
-    for tag in ("cur", "ref"):
-        b = path.buf[tag]
-        m = torch.from_numpy(U.used_mask(w.R, w.d, w.k)).to(gpu_device)
-        assert bool((b["dstats"]["row_lse"][m] >= b["dstats"]["row_max"][m]).all())
-        tt = b["dstats"]["top_tok"][m]
-        assert bool(((tt >= 0) & (tt < w.V)).all())
-        assert bool((b["tree"]["sel_score"][:, :-1] >= b["tree"]["sel_score"][:, 1:]).all())
-        aux = b["reward"]["reward_aux"]
-        assert bool((aux[:, 1] <= aux[:, 0] + 1e-5).all()) and bool((aux[:, 3] <= w.d + 1e-4).all())
-    roots = [5, 517]
-    L, n_ambig = _compare_fused(w, t, path, roots)
-    _say(f"  sampled roots {roots}: near-tie roots {n_ambig}")
-    # surrogate on the GPU's own trees / rewards for the sampled roots; gradient rows where there are any
-    cur, ref = path.buf["cur"], path.buf["ref"]
-    g_rew, g_tree, gp = U.to_np(cur["reward"]), U.to_np(cur["tree"]), U.to_np(path.ppo)
-    g_adv = path.adv.cpu().numpy()
-    np.testing.assert_allclose(g_adv, O.group_advantage(g_rew["reward"].astype(np.float64),
-                               ref["reward"]["reward"].cpu().numpy().astype(np.float64), w.m, w.delta),
-                               rtol=2e-6, atol=1e-6)
-    lse_c = cur["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
-    lse_r = ref["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
-    K = w.R // w.m
-    E = logit_error_bound(w.hidden, float(np.abs(L["D_cur"]).max()))
-    for i, r in enumerate(roots):
-        l = int(g_rew["path_len"][r])
-        lm = lm0 = 0.0
-        for s_ in range(l):
-            j = int(g_rew["path_slot"][r, s_]); tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, s_]])
-            lm += L["D_cur"][i, s_, j, tok] - lse_c[r, s_, j]
-            lm0 += L["D_ref"][i, s_, j, tok] - lse_r[r, s_, j]
-        sref = np.exp((lm - lm0) / max(l, 1))
-        assert abs(gp["ratio"][r] - sref) <= (1e-5 + 4 * E) * sref
-        for s_ in range(l):
-            if int(path.grad_slot[r, s_]) < 0:
-                continue
-            j = int(g_rew["path_slot"][r, s_]); tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, s_]])
-            x = L["D_cur"][i, s_, j]
-            c = float(gp["coef"][r])
-            ref_row = -c * np.exp(x - (x.max() + np.log(np.exp(x - x.max()).sum()))); ref_row[tok] += c
-            got = path.grad_rows[r, s_].cpu().numpy()
-            assert np.abs(got - ref_row).max() <= (1e-5 + 4 * E) * np.abs(ref_row).max() + 1e-12
-    del t, path
-    torch.cuda.empty_cache()

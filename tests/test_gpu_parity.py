@@ -41,90 +41,28 @@ def _run_full(w, tens, device, row_stride=None, V=None, ref_stats_known=True, fl
 
 
 def _compare_all(w, tens, path, V=None, roots=None, grad_scale=0.5, reward_key="reward_lse", flags=0):
-    """Stages 1-3 for the roots in `roots` (default all)."""
+    """Stages 1-3 for the roots in `roots` (default all), in this process."""
     V = V or w.V
     R = tens["D_cur"].shape[0]
     roots = list(range(R)) if roots is None else list(roots)
     sub = {n: U.logits_np(t[roots])[..., :V] for n, t in tens.items()}
-    ora = O.full_path(sub["D_cur"], sub["T_cur"], sub.get("D_ref", sub["D_cur"]), sub.get("T_ref", sub["T_cur"]),
-                      k=w.k, d=w.d, g=w.g, m=1, eta=w.eta, eps=w.eps, delta=w.delta, want_grad=False)
-    n_ambig = 0
-    for tag in (("cur", "ref") if w.full_path else ("cur",)):
-        b = path.buf[tag]
-        gd = {k: v[roots] for k, v in U.to_np(b["dstats"]).items()}
-        gt = {k: v[roots] for k, v in U.to_np(b["tstats"]).items()}
-        gpool = {k: v[roots] for k, v in U.to_np(b["pool"]).items()}
-        gtree = {k: v[roots] for k, v in U.to_np(b["tree"]).items()}
-        grew = {k: v[roots] for k, v in U.to_np(b["reward"]).items()}
-        o = ora[tag]
-        Dn = sub["D_" + tag] if "D_" + tag in sub else sub["D_cur"]
-        Tn = sub["T_" + tag] if "T_" + tag in sub else sub["T_cur"]
-        U.check_row_stats(gd, o["dstats"], Dn, w.k)                       # stage 1
-        U.check_target_stats(gt, o["tstats"])
-        pool2, tree2, rew2, path2 = U.oracle_from_gpu_stats(gd, gt, Tn, w.d, w.k, w.g, w.eta)
-        U.check_stage2(gpool, gtree, grew, pool2, tree2, rew2, path2)     # stage 2
-        margin = np.minimum(o["pool"]["min_margin"], o["tree"]["min_margin"])
-        clear = np.nonzero(margin >= U.TAU)[0]
-        n_ambig += len(roots) - len(clear)
-        U.check_stage2(gpool, gtree, grew, o["pool"], o["tree"], o["reward"], o["path"], roots=clear,
-                       exact_scores=False)                                # stage 3
+    ora, n_ambig, n_clear, n_same = U.compare_trees(w, sub, U.bundle_np(path, roots, with_ppo=False))
     return ora, n_ambig
 
 
-def _compare_ppo(w, tens, path, ora_unused=None, grad_scale=0.5, reward_key="reward_lse", flags=0):
-    """Advantage, surrogate and gradient for the whole batch (groups need all roots)."""
+def _compare_ppo(w, tens, path, ora_unused=None, grad_scale=0.5, reward_key="reward_lse", flags=0, E=0.0):
+    """Advantage, surrogate and gradient for the whole batch (groups need all roots), in this process."""
     V = path.cfg.V
     sub = {n: U.logits_np(t)[..., :V] for n, t in tens.items()}
     ora = O.full_path(sub["D_cur"], sub["T_cur"], sub["D_ref"], sub["T_ref"], k=w.k, d=w.d, g=w.g, m=w.m,
                       eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=grad_scale,
                       reward_mode=reward_key.replace("reward_", ""))
-    cur = path.buf["cur"]
-    g_tree, g_rew = U.to_np(cur["tree"]), U.to_np(cur["reward"])
-    same_tree = all(np.array_equal(g_tree[n], ora["cur"]["tree"][n]) for n in U.INT_TREE) and \
-        all(np.array_equal(g_rew[n], ora["cur"]["path"][n]) for n in U.INT_PATH) and \
-        np.array_equal(U.to_np(path.buf["ref"]["tree"])["sel_cand"], ora["ref"]["tree"]["sel_cand"])
-    # (a) the kernels on the GPU's own inputs: oracle arithmetic fed GPU rewards / trees / stats
-    g_adv = path.adv.cpu().numpy()
-    adv_same_in = O.group_advantage(g_rew["reward"].astype(np.float64),
-                                    U.to_np(path.buf["ref"]["reward"])["reward"].astype(np.float64), w.m, w.delta)
-    np.testing.assert_allclose(g_adv, adv_same_in, rtol=2e-6, atol=1e-6)
-    gd, gr = U.to_np(cur["dstats"]), U.to_np(path.buf["ref"]["dstats"])
-    gpath = {n: g_rew[n] for n in U.INT_PATH}
-    f2 = O.ppo_surrogate_fwd(gpath, g_tree, sub["D_cur"], gd["row_lse"].astype(np.float64), sub["D_ref"],
-                             gr["row_lse"].astype(np.float64), g_adv.astype(np.float64), w.m, w.eps)
-    gp = U.to_np(path.ppo)
-    for n in ("logM", "logM0", "ratio", "term"):
-        np.testing.assert_allclose(gp[n], f2[n], rtol=1e-5, atol=1e-6, err_msg=n)
-    assert np.array_equal(gp["active"], f2["active"])
-    np.testing.assert_allclose(gp["loss_group"], f2["loss_group"], rtol=1e-5, atol=1e-6)
-    np.testing.assert_allclose(gp["loss"][0], f2["loss"], rtol=1e-5, atol=1e-6)
-    # gradient rows against the oracle's own fp64 softmax (same path, advantage and ratio)
-    b2 = O.ppo_surrogate_bwd(gpath, g_tree, f2, sub["D_cur"], ora["cur"]["dstats"]["row_lse"],
-                             g_adv.astype(np.float64), w.m, grad_scale)
-    np.testing.assert_allclose(gp["coef"], b2["coef"], rtol=1e-5, atol=1e-12)
-    g_slot = path.grad_slot.cpu().numpy()
-    g_rows = path.grad_rows.cpu().numpy()
-    want_slot = np.where((b2["coef"] != 0)[:, None], b2["grad_slot"], -1)
-    assert np.array_equal(g_slot, want_slot)
-    for r in range(g_rows.shape[0]):
-        for t in range(w.d):
-            if g_slot[r, t] >= 0:
-                ref_row = b2["grad_rows"][r, t]
-                scale = np.abs(ref_row).max()
-                assert np.abs(g_rows[r, t] - ref_row).max() <= 1e-5 * scale + 1e-12, (r, t)
-            elif flags & G.GTO_FLAG_GRAD_ZERO_FILL:
-                assert not g_rows[r, t].any()
-            else:
-                assert (g_rows[r, t] == 7.0).all()
-    # (b) end to end against the pure fp64 oracle, where the trees agree
-    if same_tree:
-        sd = np.array([np.std((ora["cur"]["reward"][reward_key] - ora["ref"]["reward"][reward_key])[i:i + w.m])
-                       for i in range(0, len(g_adv), w.m)]).repeat(w.m)
-        tol = 1e-5 * (1 + np.abs(ora["adv"])) + 4e-6 * (1 + np.abs(ora["adv"])) / (sd + w.delta)
-        assert np.all(np.abs(g_adv - ora["adv"]) <= tol)
-        ok = sd > 0.05           # groups whose spread is far above the fp32 reward rounding
-        np.testing.assert_allclose(gp["ratio"], ora["ppo"]["ratio"], rtol=1e-5)
-        np.testing.assert_allclose(gp["term"][ok], ora["ppo"]["term"][ok], rtol=2e-4, atol=1e-5)
+    bundle = U.bundle_np(path, grad="dense")
+    same_tree, _, loss_group = U.compare_ppo(w, sub, bundle, ora, grad_scale=grad_scale, reward_key=reward_key,
+                                             zero_fill=bool(flags & G.GTO_FLAG_GRAD_ZERO_FILL), untouched=7.0, E=E)
+    # the batch loss is the mean of the group losses (Eq. 12 averaged over the K groups)
+    np.testing.assert_allclose(path.ppo["loss"].cpu().numpy()[0], float(np.mean(loss_group)), rtol=1e-5 + 4 * E,
+                               atol=1e-6 + 2 * w.d * E)
     return same_tree
 
 
@@ -438,94 +376,6 @@ def test_bitwise_deterministic(gpu_device):
     assert torch.equal(a.grad_slot, b.grad_slot)
     v = a.grad_slot >= 0
     assert torch.equal(a.grad_rows[v], b.grad_rows[v])
-
-
-# ------------------------------------------------------------------------------------ full-size configs
-def _properties(w, path, tag="cur"):
-    """Invariants that hold at any size (checked on every root of the full-size run)."""
-    b = path.buf[tag]
-    R = path.cfg.R
-    m = torch.from_numpy(U.used_mask(R, w.d, w.k)).to(b["dstats"]["row_lse"].device)
-    ds, tr, rw = b["dstats"], b["tree"], b["reward"]
-    assert bool((ds["row_lse"][m] >= ds["row_max"][m]).all())
-    tt = ds["top_tok"][m]
-    assert bool(((tt >= 0) & (tt < w.V)).all())
-    lp = ds["top_logp"][m]
-    assert bool((lp <= 0).all()) and bool((lp[:, :-1] >= lp[:, 1:]).all())
-    assert bool((tr["n_sel"] == min(w.g, w.C)).all())
-    assert bool((tr["sel_score"][:, :-1] >= tr["sel_score"][:, 1:]).all())
-    idx = torch.arange(w.g, device=tr["sel_parent"].device)[None, :]
-    assert bool((tr["sel_parent"] < idx).all())
-    aux = rw["reward_aux"]
-    n_leaves = rw["n_leaves"].float()
-    assert bool((aux[:, 1] <= aux[:, 0] + 1e-5).all())
-    assert bool((aux[:, 0] <= aux[:, 1] + torch.log(n_leaves) / w.eta + 1e-5).all())
-    assert bool((aux[:, 3] <= w.d + 1e-4).all()) and bool((aux[:, 2] <= aux[:, 1] + 1e-6).all())
-    assert bool(((rw["path_len"] >= 0) & (rw["path_len"] <= w.d)).all())
-
-
-@pytest.mark.parametrize("name,sample", [("vicuna13b", 8), ("llama31_8b", 6), ("qwen3_8b", 4)])
-def test_full_size_config_sampled_roots(gpu_device, name, sample):
-    w = S.CONFIGS[name]
-    R = w.chunk_roots or w.R                        # config 4 is processed in 256-root chunks
-    wr = S.scaled(w, R=R)
-    _say(f"full size {name}: R={R} V={w.V} k={w.k} d={w.d} g={w.g}")
-    want = ("D_cur", "T_cur", "D_ref", "T_ref") if w.full_path else ("D_cur", "T_cur")
-    tens = S.make_logits(wr, gpu_device, want=want)
-    _say("  inputs generated")
-    path = _run_full(wr, tens, gpu_device)
-    _say("  GPU path done")
-    _properties(wr, path, "cur")
-    if w.full_path:
-        _properties(wr, path, "ref")
-    rng = np.random.default_rng(1234)
-    roots = sorted(rng.choice(R, size=sample, replace=False).tolist())
-    _, n_ambig = _compare_all(wr, tens, path, roots=roots)
-    _say(f"  sampled roots {roots}: near-tie roots {n_ambig}")
-    if w.full_path:
-        # advantage / surrogate on the GPU's own rewards and trees, every root; gradient on sampled rows
-        cur, ref = path.buf["cur"], path.buf["ref"]
-        g_rew = U.to_np(cur["reward"])
-        g_adv = path.adv.cpu().numpy()
-        np.testing.assert_allclose(g_adv, O.group_advantage(g_rew["reward"].astype(np.float64),
-                                   ref["reward"]["reward"].cpu().numpy().astype(np.float64), w.m, w.delta),
-                                   rtol=2e-6, atol=1e-6)
-        gp = U.to_np(path.ppo)
-        g_tree = U.to_np(cur["tree"])
-        lse_c = cur["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
-        lse_r = ref["dstats"]["row_lse"].cpu().numpy().astype(np.float64)
-        K = R // w.m
-        for r in roots:
-            l = int(g_rew["path_len"][r])
-            lm = lm0 = 0.0
-            for t in range(l):
-                j = int(g_rew["path_slot"][r, t]); tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, t]])
-                lm += float(tens["D_cur"][r, t, j, tok]) - lse_c[r, t, j]
-                lm0 += float(tens["D_ref"][r, t, j, tok]) - lse_r[r, t, j]
-            s = np.exp((lm - lm0) / max(l, 1))
-            assert abs(gp["ratio"][r] - s) <= 1e-5 * s
-            A = float(g_adv[r])
-            term = min(s * A, max(1 - w.eps, min(s, 1 + w.eps)) * A)
-            assert abs(gp["term"][r] - term) <= 1e-5 * abs(term) + 1e-7
-            coef = 0.5 * (-A / (w.m * K)) * int(gp["active"][r]) * s / max(l, 1)
-            assert abs(gp["coef"][r] - coef) <= 1e-5 * abs(coef) + 1e-12
-            for t in range(l):
-                j = int(g_rew["path_slot"][r, t])
-                if gp["coef"][r] == 0:
-                    assert int(path.grad_slot[r, t]) == -1
-                    continue
-                assert int(path.grad_slot[r, t]) == j
-                tok = int(g_tree["sel_tok"][r, g_rew["path_node"][r, t]])
-                x = tens["D_cur"][r, t, j].double().cpu().numpy()
-                ref_row = -coef * np.exp(x - float(torch.logsumexp(tens["D_cur"][r, t, j].double(), 0)))
-                ref_row[tok] += coef
-                got = path.grad_rows[r, t].cpu().numpy()
-                assert np.abs(got - ref_row).max() <= 1e-5 * np.abs(ref_row).max() + 1e-12
-        np.testing.assert_allclose(gp["loss_group"], [-gp["term"][i:i + w.m].astype(np.float64).mean()
-                                                      for i in range(0, R, w.m)], rtol=1e-5, atol=1e-6)
-        np.testing.assert_allclose(gp["loss"][0], gp["loss_group"].astype(np.float64).mean(), rtol=1e-5, atol=1e-7)
-    del tens, path
-    torch.cuda.empty_cache()
 
 
 # ------------------------------------------------------------------------------------ token-level loss

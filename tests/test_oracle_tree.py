@@ -183,3 +183,71 @@ def test_margin_audit_flags_near_ties_only():
     D3[0, 0, 0, 1], D3[0, 1, 0, 2], D3[0, 1, 1, 3] = 0.0, 0.0, 0.0
     _, pool3, tree3 = _build(D3, k, d, 5)          # kept: the chain 1 -> 2, then -inf candidates by index
     assert tree3["sel_cand"][0].tolist() == [0, 2, 1, 3, 4] and tree3["min_margin"][0] == np.inf
+
+
+def _two_candidate_pool(lp_a, lp_b, logit_err):
+    """d = 1, k = 2: the root's two children are the whole pool; their scores are their log-probabilities."""
+    top_tok = np.array([[[[0, 1], [0, 0]]]], dtype=np.int32)                    # [R=1, d=1, k=2, k=2]
+    lp64 = np.array([[[[lp_a, lp_b], [0.0, 0.0]]]])
+    logit = np.array([[[[1.0, 0.5], [0.0, 0.0]]]])                              # distinct logits: not an exact tie
+    return O.expand_tree(top_tok, lp64.astype(np.float32), 1, 2, lp64, logit, logit_err)
+
+
+def test_logit_error_budget_straddle():
+    """The audit's budget with an absolute logit error E (fused LM-head workload): each log-probability may be
+    off by 2 E (its logit by E, its row's log-sum-exp by E), on top of the fp32 terms.  Two candidates whose
+    gap is just above 2 x (budget_a + budget_b) are clear, just below it they are a near tie; without E the
+    same gap is clear by a wide margin."""
+    E = 1e-3
+    lp_a = -0.5
+    fp32_terms = lambda lp: float(np.spacing(np.float32(abs(lp)))) + 2.0 ** -23
+    for factor, clear in ((1.02, True), (0.98, False)):
+        # solve gap = factor * 2 * (budget_a + budget_b); the budget of b depends (weakly) on lp_b through its ulp
+        gap = factor * 2.0 * (fp32_terms(lp_a) + fp32_terms(lp_a - 8.0 * E) + 4.0 * E)
+        pool = _two_candidate_pool(lp_a, lp_a - gap, E)
+        tree = O.select_topg(pool, 1, audit=True)
+        assert (tree["min_margin"][0] >= 1.0) == clear, (factor, tree["min_margin"][0])
+        assert abs(tree["min_margin"][0] - factor) < 0.01
+        # the budget itself: fp32 terms + 2 E per candidate
+        assert abs(pool["cand_err"][0, 0] - (fp32_terms(lp_a) + 2 * E)) < 1e-12
+        wide = O.select_topg(_two_candidate_pool(lp_a, lp_a - gap, 0.0), 1, audit=True)
+        assert wide["min_margin"][0] > 1e3
+
+
+def test_logit_error_budget_is_sound_against_perturbed_logits():
+    """What the budget is for, checked by brute force: if the audit calls a root clear (ratio >= 1) under a
+    logit error E, then no perturbation of the log-probabilities by up to 2 E each (all 2^C corners, fp32
+    scores recomputed) changes the kept set or its order; and a gap smaller than the two candidates' combined
+    2 E allowances is always flagged."""
+    rng = np.random.default_rng(11)
+    E = 2e-3
+    k, d = 4, 1
+    n_clear = n_flagged = 0
+    for it in range(300):
+        lp = -np.sort(rng.uniform(0.05, 0.12, size=k)).astype(np.float64) - np.arange(k) * rng.choice([0.0, 0.004, 0.03])
+        top_tok = np.zeros((1, d, k, k), dtype=np.int32)
+        top_tok[0, 0, 0] = np.arange(k)
+        lp64 = np.zeros((1, d, k, k))
+        lp64[0, 0, 0] = lp
+        logit = np.zeros((1, d, k, k))
+        logit[0, 0, 0] = 5.0 - np.arange(k)
+        pool = O.expand_tree(top_tok, lp64.astype(np.float32), d, k, lp64, logit, E)
+        tree = O.select_topg(pool, 2, audit=True)
+        base = tree["sel_cand"][0].tolist()
+        flips = False
+        for corner in range(1 << k):
+            delta = np.array([(2 * E if (corner >> i) & 1 else -2 * E) for i in range(k)])
+            pert = lp64.copy()
+            pert[0, 0, 0] = lp + delta
+            p2 = O.expand_tree(top_tok, pert.astype(np.float32), d, k)
+            if O.select_topg(p2, 2)["sel_cand"][0].tolist() != base:
+                flips = True
+                break
+        gaps = np.abs(np.diff(lp[:3]))                    # the audited neighbours: ranks (0,1) and (1,2)
+        if tree["min_margin"][0] >= 1.0:
+            n_clear += 1
+            assert not flips, (it, lp, tree["min_margin"][0])
+        if gaps.min() < 4 * E:                            # inside the two candidates' allowances: must be flagged
+            n_flagged += 1
+            assert tree["min_margin"][0] < 1.0, (it, lp)
+    assert n_clear > 20 and n_flagged > 20

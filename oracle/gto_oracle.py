@@ -90,6 +90,17 @@ def fused_logits(H: np.ndarray, W_vh: np.ndarray) -> np.ndarray:
     return out
 
 
+def fp32_accumulation_error(hidden: int, max_abs_logit: float) -> float:
+    """Absolute error to grant a logit that the other side accumulates in fp32 on the matrix cores, where this
+    oracle accumulates in fp64 (the `logit_err` of row_margins and expand_tree).  The fp32 accumulator is
+    rounded once per step of 16 products, i.e. hidden / 16 times; each rounding is uniform within half an ulp
+    of the running sum, which stays below the largest |logit|, so one rounding has a standard deviation of at
+    most ulp32(max |logit|) / sqrt(12), and their sum sqrt(hidden / 16) times that.  The bound is six such
+    standard deviations: a full-size comparison checks ~1e5 logits against it, and a bound that one of them
+    may exceed by chance would be useless (the worst case, hidden / 16 half-ulps, is never approached)."""
+    return 6.0 * _ulp32(max_abs_logit) * math.sqrt(max(hidden / 16.0, 1.0) / 12.0)
+
+
 def row_margins(logits: np.ndarray, k: int, logit_err: float) -> np.ndarray:
     """Near-tie audit of the per-row top-k when the logits themselves carry an error of up to
     `logit_err` (fp32 accumulation on the other side): per root, the smallest gap between

@@ -1,9 +1,13 @@
 """CPU-only worker processes that run the oracle over many roots in parallel.
 
+TEST INFRASTRUCTURE ONLY, like the oracle itself: used by the full-size parity tests and by the benchmark's
+cpu_baseline leg, never by the product path.  It holds none of the method's arithmetic.
+
 The full-size parity tests compare every root of a batch (or whole groups of it) with the oracle, which
 takes about a second per root at V = 128256; fanned out over the GPU machine's host cores a whole batch takes
-about a minute.  The workers are forked from the test process BEFORE it makes its first GPU call (conftest
-starts them when collection has finished), they never touch the GPU, and they run the oracle as it stands.
+about a minute.  The workers are forked from the calling process BEFORE it makes its first GPU call (the
+tests' conftest starts them when collection has finished, bench.py at start-up), they never touch the GPU,
+and they run the oracle as it stands.
 
 Data travels through one anonymous shared memory mapping (the "arena") created before the fork: the test
 process copies a slice of the device tensors into it, the workers read it in place.  Small things (the
@@ -104,14 +108,52 @@ def arena_get(handle, rows=None) -> np.ndarray:
     return a
 
 
-def run(func, jobs, label=""):
+def run(func, jobs, label="", quiet=False):
     """Run func(job) for every job on the workers; results in job order.  Prints one line per finished job
-    (the work's own progress)."""
+    (the work's own progress): to stdout, or to stderr when `quiet` (a caller whose stdout is its result)."""
     t0 = time.time()
     pending = [_pool.apply_async(func, (job,)) for job in jobs]
     out = []
     for i, p in enumerate(pending):
         out.append(p.get())
-        print(f"    {label} job {i + 1}/{len(jobs)} done at {time.time() - t0:.1f} s", flush=True)
-    sys.stdout.flush()
+        print(f"    {label} job {i + 1}/{len(jobs)} done at {time.time() - t0:.1f} s", flush=True,
+              file=sys.stderr if quiet else sys.stdout)
     return out
+
+
+def timed_full_path(job):
+    """Worker job of the benchmark's cpu_baseline leg: the oracle's whole path (both trees, rewards, advantage,
+    surrogate, gradient; or build + reward + walk of one tree for a reward-only workload) over the roots
+    whose logits sit in the arena.  Returns the seconds it took, the trees it scored and, from the oracle's
+    near-tie audit, how many of them hold a ranking decision within fp32 rounding (several results correct).
+    job: logits {name: handle}, V, k, d, g, m, eta, eps, delta, full_path; for the fused workload instead
+    hidden {H_cur, H_ref} and heads {W_draft, W_target} (fp64)."""
+    from oracle import gto_oracle as O
+    t0 = time.time()
+    k, d, g = job["k"], job["d"], job["g"]
+    if "hidden" in job:
+        H = {n: arena_get(h) for n, h in job["hidden"].items()}
+        Wd, Wt = arena_get(job["heads"]["W_draft"]), arena_get(job["heads"]["W_target"])
+        L = {"D_cur": O.fused_logits(H["H_cur"], Wd), "T_cur": O.fused_logits(H["H_cur"], Wt),
+             "D_ref": O.fused_logits(H["H_ref"], Wd), "T_ref": O.fused_logits(H["H_ref"], Wt)}
+        # the other side accumulates these logits in fp32: the audit is told by how much they may differ
+        job = dict(job, logit_err=O.fp32_accumulation_error(Wd.shape[1], max(float(np.abs(v).max()) for v in L.values())))
+    else:
+        L = {n: arena_get(h)[..., :job["V"]] for n, h in job["logits"].items()}
+    n = L["D_cur"].shape[0]
+    if job["full_path"]:
+        out = O.full_path(L["D_cur"], L["T_cur"], L["D_ref"], L["T_ref"], k=k, d=d, g=g, m=job["m"], eta=job["eta"],
+                          eps=job["eps"], delta=job["delta"], grad_scale=0.5, logit_err=job.get("logit_err", 0.0))
+        margins = [np.minimum(out[t]["pool"]["min_margin"], out[t]["tree"]["min_margin"]) for t in ("cur", "ref")]
+        trees = 2 * n
+    else:
+        ds = O.draft_row_stats(L["D_cur"], k)
+        pool = O.expand_tree(ds["top_tok"], ds["top_logp32"], d, k, ds["top_logp64"], ds["top_logit"])
+        tree = O.select_topg(pool, g, audit=True)
+        ts = O.target_row_stats(L["T_cur"])
+        O.tree_reward(tree, L["T_cur"], ts["t_lse"], job["eta"])
+        O.accepted_path(tree, ts["t_argmax"], d)
+        margins = [np.minimum(pool["min_margin"], tree["min_margin"])]
+        trees = n
+    near = int(sum((mg < 1.0).sum() for mg in margins))
+    return dict(seconds=time.time() - t0, trees=trees, near_ties=near)

@@ -24,12 +24,12 @@ def pytest_collection_finish(session):
             return
     except Exception:
         return
-    import oracle_pool
+    from oracle import pool as oracle_pool
     oracle_pool.start()
 
 
 def pytest_sessionfinish(session, exitstatus):
-    import oracle_pool
+    from oracle import pool as oracle_pool
     oracle_pool.stop()
 
 
@@ -51,7 +51,7 @@ def gpu_device():
 
 @pytest.fixture(scope="session")
 def oracle_workers(gpu_device):
-    import oracle_pool
+    from oracle import pool as oracle_pool
     if not oracle_pool.started():
         pytest.skip("oracle workers were not started (no GPU test was collected)")
     return oracle_pool

@@ -292,15 +292,7 @@ def slice_grad_scale(grad_scale, n_slice_roots, n_batch_roots):
 
 
 # ------------------------------------------------------------------------------------------------ fused variant
-def logit_error_bound(hidden, max_abs_logit):
-    """Absolute error granted to a logit that the matrix cores accumulate in fp32.  The accumulator is rounded
-    once per step of 16 products, i.e. hidden / 16 times; each rounding is uniform within half an ulp of the
-    running sum, which stays below the largest |logit|, so one rounding has a standard deviation of at most
-    ulp32(max |logit|) / sqrt(12) and their sum sqrt(hidden / 16) times that.  The bound is six such standard
-    deviations: a full-size run checks ~1e5 logits against it, and a bound that one of them may exceed by
-    chance would make the test flaky (the worst case, hidden / 16 half-ulps, is never approached)."""
-    ulp = float(np.spacing(np.float32(max_abs_logit)))
-    return 6.0 * ulp * math.sqrt(max(hidden / 16.0, 1.0) / 12.0)
+logit_error_bound = O.fp32_accumulation_error      # E: see the oracle for the derivation
 
 
 def compare_trees_fused(w, L, bundle, ora=None, E=None):

@@ -1,4 +1,4 @@
-"""Jobs the CPU-only oracle workers run (see oracle_pool.py): the oracle over one slice of roots, compared
+"""Jobs the CPU-only oracle workers run (see oracle/pool.py): the oracle over one slice of roots, compared
 with the GPU's results for that slice.  A job returns a small verdict; it never raises (a failure comes
 back as text, so that the test process can report the slice and go on to read the other verdicts)."""
 import time
@@ -7,7 +7,7 @@ import traceback
 import numpy as np
 
 import gpu_util as U
-import oracle_pool as P
+from oracle import pool as P
 from oracle import gto_oracle as O
 
 

@@ -1,7 +1,7 @@
 """Parity at the full sizes of the five configurations, in the launch configuration bench.py times
 (target-row pruning on; the fourth configuration in 256-root chunks alternating between two streams).
 
-The oracle runs over the batch on CPU-only worker processes (oracle_pool.py), one slice of whole advantage
+The oracle runs over the batch on CPU-only worker processes (oracle/pool.py), one slice of whole advantage
 groups per job, so that every stage - row statistics, tree, reward, verification walk, advantage, surrogate
 and gradient rows - is compared through the oracle's own functions, for every root of configurations 2 and
 3 and for whole groups of every chunk of configuration 4 and of the fused configuration.  Each test prints

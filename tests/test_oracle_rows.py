@@ -79,3 +79,25 @@ def test_fused_logits_is_the_plain_dot_product_and_row_margins_flag_close_tops()
     X[0, 0, 0] = [5.0, 4.0, 3.0, 2.9999, 0.0, -1.0]
     assert O.row_margins(X, 2, 1e-3)[0] == pytest.approx(1.0 / 2e-3)       # top-3 gaps: 1, 1
     assert O.row_margins(X, 3, 1e-3)[0] < 1.0                              # 3 vs 2.9999 is inside the error
+
+
+def test_fp32_accumulation_error_bound_covers_simulated_fp32_sums():
+    """The error granted to fp32-accumulated logits: simulate the accumulation (exact 16-product partial sums
+    added to an fp32 accumulator, one rounding each) against the fp64 sum for many rows; the largest observed
+    error must stay below the bound, and the bound must not be absurdly loose (within ~3x of the worst of
+    20 000 samples at six standard deviations)."""
+    import numpy as np
+    from oracle import gto_oracle as O
+    rng = np.random.default_rng(3)
+    hidden, n = 2048, 20000
+    h = rng.standard_normal((n, hidden)).astype(np.float32)
+    wv = (rng.standard_normal((n, hidden)) * 0.05).astype(np.float32)
+    prod = h.astype(np.float64) * wv.astype(np.float64)
+    exact = prod.sum(axis=1)
+    acc = np.zeros(n, dtype=np.float32)
+    for s in range(0, hidden, 16):
+        acc = (acc.astype(np.float64) + prod[:, s:s + 16].sum(axis=1)).astype(np.float32)
+    err = np.abs(acc.astype(np.float64) - exact)
+    bound = O.fp32_accumulation_error(hidden, float(np.abs(exact).max()))
+    assert err.max() < bound
+    assert bound < 6.0 * err.max()

@@ -40,14 +40,11 @@ __device__ __forceinline__ void wait_vmcnt() {
   if (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
 }
 
-// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at
-// lds_addr + 16 l (lds_addr is wave-uniform and travels in M0); counted by vmcnt.
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at lds_addr + 16 l
+// (lds_addr is wave-uniform; the compiler moves it into M0); counted by vmcnt.
 __device__ __forceinline__ void load_to_lds16(unsigned lds_addr, const void *g) {
-  unsigned keep;
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-               : "=&s"(keep)
-               : "s"(lds_addr), "v"(g)
-               : "memory");
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                   (__attribute__((address_space(3))) void *)(uintptr_t)lds_addr, 16, 0, 0);
 }
 
 // index of the statistics entry (= logits slot) of the q-th used row of root r
@@ -84,99 +81,121 @@ __device__ __forceinline__ void list_insert(float (&v)[KT], int (&id)[KT], float
   }
 }
 
-// acc += A . B^T over kt_count k slabs of 32, for the 256 x 256 tile of the workgroup; wave (wm, wn)
-// owns the 128 x 128 quadrant.  pa(s, j) / pb(s, j) give this lane's global address for load j
-// (16-row group 64 wave + 16 j) of slab s of the row operand / the column operand: the 16 bytes of
-// row ld_row + 16 j at k unit ld_unit of that slab (see the callers).  Every wave of the workgroup
-// calls this with the same kt_count; on return all fragment reads of the caller's wave are done.
-template <class PA, class PB>
+// ---- the GEMM main loop: acc += A . B^T over kt_count k slabs of 32, for the 256 x 256 tile of the
+// workgroup; wave (wm, wn) owns the 128 x 128 quadrant as 4 x 4 MFMA 32x32x16 tiles.
+//
+// K slab s lands in ring stage s % 4 (global memory -> LDS directly); every wave issues 4 loads per
+// operand and slab (load j = the 16-row group 64 wave + 16 j).  The matrix pipe is the unit to keep busy
+// and this wave is the only one on its SIMD, so the instruction stream is laid out by hand: every MFMA is
+// followed by at most one memory instruction (pinned by scheduling barriers), which issues while the
+// MFMA executes.  One slab:
+//   first half  (k units 0, 1): after MFMA 0..7 the fragment reads of the second half (the four W
+//               fragments first: its first MFMA row needs them all); after MFMA 8..11 the W loads of slab
+//               s+2; then the wait until slab s+1 has landed, and the barrier
+//   second half (k units 2, 3): after MFMA 0..7 the first-half fragments of slab s+1; after MFMA 8..11
+//               the hidden-state loads of slab s+3
+struct SlabRing {
+  unsigned wbase;              // LDS byte address of this wave's 4 KB landing area inside stage 0
+  const unsigned char *ldsb;   // the ring
+  int fa_base, fb_base;        // this lane's fragment byte offsets inside a stage (k units 0 / 1)
+};
+
+template <bool LB, bool LA, bool NEXT>
+__device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
+                                          const SlabRing &r, const uint16_t *(&ap)[4], const uint16_t *(&bp)[4],
+                                          int stage) {
+  const int s1 = (stage + 1) % FNST, s2 = (stage + 2) % FNST, s3 = (stage + 3) % FNST;
+  const unsigned char *sS = r.ldsb + stage * FSTAGE_B;
+  const unsigned char *nS = r.ldsb + s1 * FSTAGE_B;
+#pragma unroll
+  for (int idx = 0; idx < 16; ++idx) {
+    const int i = idx >> 2, j = idx & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
+    if (idx < 4) {
+      fb[1][idx] = *reinterpret_cast<const bf16x8 *>(sS + (r.fb_base ^ 32) + idx * 32 * FROWB);
+    } else if (idx < 8) {
+      fa[1][idx - 4] = *reinterpret_cast<const bf16x8 *>(sS + (r.fa_base ^ 32) + (idx - 4) * 32 * FROWB);
+    } else if (idx < 12) {
+      // stage s+2 was last read as slab s-2: every wave passed the barrier of slab s-1 after that
+      if (LB) {
+        load_to_lds16(r.wbase + s2 * FSTAGE_B + FBM * FROWB + (idx - 8) * 1024, bp[idx - 8]);
+        bp[idx - 8] += FBK;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (NEXT) {
+    // this wave's share of slab s+1 has landed when at most the 8 loads of slab s+2 are still out; the
+    // barrier extends that to the other waves' shares, and tells that every wave is past its reads of
+    // slab s-1, whose stage the next loads overwrite
+    if (LB) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int idx = 0; idx < 16; ++idx) {
+    const int i = idx >> 2, j = idx & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
+    if (NEXT) {
+      if (idx < 4) fb[0][idx] = *reinterpret_cast<const bf16x8 *>(nS + r.fb_base + idx * 32 * FROWB);
+      else if (idx < 8) fa[0][idx - 4] = *reinterpret_cast<const bf16x8 *>(nS + r.fa_base + (idx - 4) * 32 * FROWB);
+    }
+    if (idx >= 8 && idx < 12) {
+      if (LA) {
+        load_to_lds16(r.wbase + s3 * FSTAGE_B + (idx - 8) * 1024, ap[idx - 8]);
+        ap[idx - 8] += FBK;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// ap[j] / bp[j]: this lane's global address, in slab 0, for load j of the row operand / the column
+// operand: the 16 bytes of row ld_row + 16 j at k unit ld_unit (see the callers); both advance by one slab
+// per load.  Every wave of the workgroup calls this with the same kt_count >= 1; on return all fragment
+// reads of the caller's wave are done and nothing of this call is in flight.
 __device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds, unsigned wbase, int lane, int wm,
-                                              int wn, int kt_count, PA pa, PB pb) {
-  // k slab s lands in stage s % FNST; every wave issues 4 loads per operand and slab (load j = one
-  // 16-row group)
-  auto issue_a = [&](int s_, int j) {
-    load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + j * 1024, pa(s_, j));
-  };
-  auto issue_b = [&](int s_, int j) {
-    load_to_lds16(wbase + (unsigned)(s_ % FNST) * (unsigned)FSTAGE_B + FBM * FROWB + j * 1024, pb(s_, j));
-  };
-  __syncthreads();                           // previous tile's epilogue no longer reads the staging area
+                                              int wn, int kt_count, const uint16_t *(&ap)[4],
+                                              const uint16_t *(&bp)[4]) {
+  SlabRing r;
+  r.wbase = wbase;
+  r.ldsb = reinterpret_cast<const unsigned char *>(lds);
+  // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
+  // 16-byte unit 2 h + (lane >> 5) of k half h sits at unit ^ ((row / 4) % 4).
+  const int fsw = ((lane >> 5) ^ ((lane >> 2) & 3)) * 16;
+  r.fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
+  r.fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
+  __syncthreads();                           // the previous user of the ring (an epilogue's staging area) is done
   // prologue: slabs 0 and 1 and the hidden-state half of slab 2 (its W half follows in the loop)
 #pragma unroll
   for (int s_ = 0; s_ < 2; ++s_)
     if (s_ < kt_count) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) issue_a(s_, j);
+      for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + s_ * FSTAGE_B + j * 1024, ap[j]); ap[j] += FBK; }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) issue_b(s_, j);
+      for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + s_ * FSTAGE_B + FBM * FROWB + j * 1024, bp[j]); bp[j] += FBK; }
     }
   if (2 < kt_count) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) issue_a(2, j);
+    for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + 2 * FSTAGE_B + j * 1024, ap[j]); ap[j] += FBK; }
     wait_vmcnt<12>();                        // slab 0 landed; slab 1 and half of slab 2 in flight
   } else {
     wait_vmcnt<0>();
   }
   __syncthreads();
-
-  // Fragment byte offsets of this lane inside a stage: row (lane & 31) of each 32-row tile; the
-  // 16-byte unit 2 h + (lane >> 5) of k half h sits at unit ^ ((row / 4) % 4).
-  const int fsw = ((lane >> 5) ^ ((lane >> 2) & 3)) * 16;
-  const int fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
-  const int fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
-  const unsigned char *ldsb = reinterpret_cast<const unsigned char *>(lds);
   bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    fa[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fa_base + t * 32 * FROWB);
-    fb[0][t] = *reinterpret_cast<const bf16x8 *>(ldsb + fb_base + t * 32 * FROWB);
+    fa[0][t] = *reinterpret_cast<const bf16x8 *>(r.ldsb + r.fa_base + t * 32 * FROWB);
+    fb[0][t] = *reinterpret_cast<const bf16x8 *>(r.ldsb + r.fb_base + t * 32 * FROWB);
   }
-  // One k slab: 16 MFMAs per half, as four rows of four.  Between the rows sit one load and two
-  // fragment reads, so that the matrix pipe does not wait for their issue and the 32 loads a
-  // workgroup issues per slab reach the texture path evenly spread:
-  //   first half  : W loads of slab kt+2, fragments of the second half of slab kt
-  //   between     : wait until slab kt+1 has landed, barrier
-  //   second half : hidden-state loads of slab kt+3, first fragments of slab kt+1
-  for (int kt = 0; kt < kt_count; ++kt) {
-    const unsigned char *sS = ldsb + (kt % FNST) * FSTAGE_B;
-    const bool has_next = kt + 1 < kt_count;
-    const bool load_b = kt + 2 < kt_count;
-    const bool load_a = kt + 3 < kt_count;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // stage (kt+2) % 4 was last read as slab kt-2: every wave passed the barrier of slab kt-1 after that
-      if (load_b) issue_b(kt + 2, i);
-      fa[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fa_base ^ 32) + i * 32 * FROWB);
-      fb[1][i] = *reinterpret_cast<const bf16x8 *>(sS + (fb_base ^ 32) + i * 32 * FROWB);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (has_next) {
-      // this wave's share of slab kt+1 has landed when at most the 8 loads of slab kt+2 are still
-      // out; the barrier extends that to the other waves' shares, and tells that every wave is
-      // past its reads of slab kt-1, whose stage the next loads overwrite
-      if (load_b) wait_vmcnt<8>();
-      else wait_vmcnt<0>();
-      __syncthreads();
-    }
-    const unsigned char *nS = ldsb + ((kt + 1) % FNST) * FSTAGE_B;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (load_a) issue_a(kt + 3, i);
-      if (has_next) {
-        fa[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fa_base + i * 32 * FROWB);
-        fb[0][i] = *reinterpret_cast<const bf16x8 *>(nS + fb_base + i * 32 * FROWB);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
+  // slabs whose three successors exist run with every load enabled; the last three drop them one by one
+  int kt = 0;
+  for (; kt + 3 < kt_count; ++kt) slab_step<true, true, true>(acc, fa, fb, r, ap, bp, kt & 3);
+  if (kt + 2 < kt_count) { slab_step<true, false, true>(acc, fa, fb, r, ap, bp, kt & 3); ++kt; }
+  if (kt + 1 < kt_count) { slab_step<false, false, true>(acc, fa, fb, r, ap, bp, kt & 3); ++kt; }
+  slab_step<false, false, false>(acc, fa, fb, r, ap, bp, kt & 3);
 }
 
 enum FusedMode { kFusedStats = 0, kFusedBwd = 1, kFusedPlanes = 2, kFusedStore = 3 };
@@ -280,9 +299,12 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count,
-                  [&](int s_, int j) { return a_ptr[j] + s_ * FBK; },
-                  [&](int s_, int j) { return b_ptr[j] + s_ * FBK; });
+    {
+      const uint16_t *ap[4], *bp[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { ap[j] = a_ptr[j]; bp[j] = b_ptr[j]; }
+      tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count, ap, bp);
+    }
     __syncthreads();                           // all fragment reads done before the staging area is written
 
     // ---- epilogue: four 64-column quarters through the staging area; thread t owns row t
@@ -661,15 +683,22 @@ __global__ __launch_bounds__(256) void k_fused_dh(FusedDhArgs a) {
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count,
-                [&](int s_, int j) {
-                  const int sg = s0 + s_;
-                  return (sg < nks) ? a_hi[j] + sg * FBK : a_lo[j] + (sg - nks) * FBK;
-                },
-                [&](int s_, int j) {
-                  const int sg = s0 + s_;
-                  return b_ptr[j] + ((sg < nks) ? sg : sg - nks) * FBK;
-                });
+  // the split's slabs [s0, s0 + kt_count) of the contraction over [hi plane | lo plane]: the part inside the
+  // hi plane, then the part inside the lo plane, each a contiguous k range of both operands
+  const int n_hi = max(0, min(s0 + kt_count, nks) - s0);
+  if (n_hi > 0) {
+    const uint16_t *ap[4], *bp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { ap[j] = a_hi[j] + (int64_t)s0 * FBK; bp[j] = b_ptr[j] + (int64_t)s0 * FBK; }
+    tile_mainloop(acc, lds, wbase, lane, wm, wn, n_hi, ap, bp);
+  }
+  if (kt_count - n_hi > 0) {
+    const int l0 = max(s0, nks) - nks;
+    const uint16_t *ap[4], *bp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { ap[j] = a_lo[j] + (int64_t)l0 * FBK; bp[j] = b_ptr[j] + (int64_t)l0 * FBK; }
+    tile_mainloop(acc, lds, wbase, lane, wm, wn, kt_count - n_hi, ap, bp);
+  }
   float *out = a.partial + (int64_t)split * a.M * a.hidden_dim;
 #pragma unroll
   for (int i = 0; i < 4; ++i)

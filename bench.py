@@ -272,7 +272,7 @@ def run_fused(name, args, steps, warmup, P, torch, S, G, cpu_roots, practical_pe
     want_dh = w.w_corr > 0 and not args.no_extras       # the hidden-state backward has rows only with agreeing heads
     path = GtoFusedPath(R=w.R, d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m, device=dev,
                         eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5,
-                        flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE, fused_chunks=args.fused_chunks,
+                        flags=0 if args.no_prune else G.GTO_FLAG_TARGET_PRUNE, fused_groups=args.fused_groups,
                         fused_layout=args.fused_layout, want_dh=want_dh)
     W_hv = t["W_draft"].t().contiguous() if want_dh else None
 
@@ -391,7 +391,7 @@ def main():
     ap.add_argument("--headline-only", action="store_true", help="skip all_configs")
     ap.add_argument("--roots", type=int, default=0, help="override the number of roots (debug)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per row in the row kernels (tuning)")
-    ap.add_argument("--fused-chunks", type=int, default=0, help="fused variant: vocabulary chunks per row block (tuning)")
+    ap.add_argument("--fused-groups", type=int, default=0, help="fused variant: vocabulary chunks per row block (tuning)")
     ap.add_argument("--fused-layout", type=int, default=0, help="fused variant: 0 per-XCD patches, 1 row-major (tuning)")
     ap.add_argument("--no-prune", action="store_true",
                     help="stream every used target row instead of only those the kept tree refers to")

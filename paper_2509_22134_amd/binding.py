@@ -29,7 +29,7 @@ class gto_config(C.Structure):
                 ("dtype", C.c_int32), ("row_stride", C.c_int64), ("group_size", C.c_int32),
                 ("reward_mode", C.c_int32), ("eta", C.c_float), ("eps", C.c_float), ("delta", C.c_float),
                 ("grad_scale", C.c_float), ("flags", C.c_int32), ("path_mode", C.c_int32),
-                ("waves_per_row", C.c_int32), ("fused_chunks", C.c_int32), ("fused_layout", C.c_int32),
+                ("waves_per_row", C.c_int32), ("fused_groups", C.c_int32), ("fused_layout", C.c_int32),
                 ("reserved", C.c_int32)]
 
     @property
@@ -134,11 +134,11 @@ def lib():
 
 def make_config(*, R, d, k, g, V, dtype, row_stride=None, group_size=1, reward_mode=GTO_REWARD_LSE,
                 eta=1.0, eps=0.2, delta=1e-6, grad_scale=1.0, flags=0, path_mode=0, waves_per_row=0,
-                fused_chunks=0, fused_layout=0) -> gto_config:
+                fused_groups=0, fused_layout=0) -> gto_config:
     if isinstance(dtype, torch.dtype):
         dtype = GTO_BF16 if dtype == torch.bfloat16 else GTO_F32
     return gto_config(R, d, k, g, V, dtype, V if row_stride is None else row_stride, group_size, reward_mode,
-                      eta, eps, delta, grad_scale, flags, path_mode, waves_per_row, fused_chunks, fused_layout, 0)
+                      eta, eps, delta, grad_scale, flags, path_mode, waves_per_row, fused_groups, fused_layout, 0)
 
 
 # ------------------------------------------------------------------ output containers (torch = memory only)

@@ -145,9 +145,8 @@ int check_cfg(const gto_config *c, bool need_group) {
     return GTO_E_MODE;
   const int wpr = c->waves_per_row;
   if (!(wpr == 0 || wpr == 1 || wpr == 2 || wpr == 4 || wpr == 8)) return GTO_E_MODE;
-  if (c->fused_chunks < 0 || c->fused_chunks > 64 || (c->fused_layout != 0 && c->fused_layout != 1) ||
-      c->reserved != 0)
-    return GTO_E_MODE;
+  if (c->fused_layout != 0 && c->fused_layout != 1) return GTO_E_MODE;
+  if (c->fused_groups < 0 || c->fused_groups > (c->fused_layout == 0 ? 8 : 16) || c->reserved != 0) return GTO_E_MODE;
   if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L && c->path_mode != GTO_PATH_SAMPLED)
     return GTO_E_MODE;
   if (need_group && (c->group_size < 1 || c->R % c->group_size != 0)) return GTO_E_SHAPE;
@@ -317,7 +316,7 @@ constexpr int kFusedMaxK = 16;
 
 struct FusedPlan {
   int64_t M;
-  int m_blocks, n_tiles, n_chunks, tiles_per_chunk;
+  int n_tiles, groups, patch_rows, patch_cols, n_slots;
   size_t off_s, off_m, off_c, off_v, off_i, bytes;
 };
 
@@ -330,22 +329,18 @@ int check_fused(const gto_config *c, const void *hidden, int hidden_dim, const v
   return GTO_OK;
 }
 
-// Rows are processed in blocks of 256; the vocabulary (tiles of 256 tokens) is split into chunks
-// so that there are at least ~8 workgroups per compute unit.
+// Launch geometry of the row pass (see the work distribution in gto_fused.hip): `groups` groups of
+// patch_rows x patch_cols workgroups, each row with groups * patch_cols partial results.  By default 8 groups
+// of 4 x 8: one group per XCD, one workgroup per compute unit.
 FusedPlan fused_plan(const gto_config *c, int64_t M, int ktop) {
-  const int V = c->V;
   FusedPlan p{};
   p.M = M;
-  p.m_blocks = (int)((M + 255) / 256);
-  p.n_tiles = (V + 255) / 256;
-  // aim at ~14 workgroups per compute unit; a multiple of 8 chunks fills the per-XCD patches
-  int nc = c->fused_chunks > 0 ? c->fused_chunks : (((3584 + p.m_blocks - 1) / p.m_blocks + 7) / 8) * 8;
-  if (nc > 64) nc = 64;
-  if (nc > p.n_tiles) nc = p.n_tiles;
-  if (nc < 1) nc = 1;
-  p.tiles_per_chunk = (p.n_tiles + nc - 1) / nc;
-  p.n_chunks = (p.n_tiles + p.tiles_per_chunk - 1) / p.tiles_per_chunk;
-  const size_t rows = (size_t)M * p.n_chunks;
+  p.n_tiles = (c->V + 255) / 256;
+  p.groups = c->fused_groups > 0 ? c->fused_groups : 8;
+  p.patch_rows = c->fused_layout == 0 ? 4 : 8;
+  p.patch_cols = c->fused_layout == 0 ? 8 : 4;
+  p.n_slots = p.groups * p.patch_cols;
+  const size_t rows = (size_t)M * p.n_slots;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   p.off_s = 0;
   p.off_m = up(p.off_s + rows * sizeof(double));
@@ -354,6 +349,10 @@ FusedPlan fused_plan(const gto_config *c, int64_t M, int ktop) {
   p.off_i = up(p.off_v + rows * ktop * sizeof(float));
   p.bytes = up(p.off_i + rows * ktop * sizeof(int32_t));
   return p;
+}
+
+void set_geometry(gto::FusedArgs &a, const FusedPlan &p) {
+  a.n_tiles = p.n_tiles; a.groups = p.groups; a.patch_rows = p.patch_rows; a.patch_cols = p.patch_cols;
 }
 
 // Workspace of the fused calls: [partials of the row pass | gathered single logits].
@@ -418,8 +417,7 @@ int run_fused_rows(const gto_config *c, const void *hidden, int hidden_dim, cons
   gto::FusedArgs a{};
   a.hidden = hidden; a.w = w; a.hidden_dim = hidden_dim; a.V = c->V; a.rho = rows_per_root(c); a.d = c->d;
   a.kslots = c->k; a.ktop = ktop; a.M = M; a.m_dev = n_dev; a.row_list = row_list; a.out_by_list = out_by_list;
-  a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-  a.xcd_patches = c->fused_layout == 0;
+  set_geometry(a, p);
   a.part_s = reinterpret_cast<double *>(base + p.off_s);
   a.part_m = reinterpret_cast<float *>(base + p.off_m);
   a.part_c = reinterpret_cast<float *>(base + p.off_c);
@@ -780,8 +778,7 @@ int gto_ppo_surrogate_bwd_fused(const gto_config *cfg, const gto_tree *tree_cur,
   gto::FusedArgs a{};
   a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
   a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
-  a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-  a.xcd_patches = cfg->fused_layout == 0;
+  set_geometry(a, p);
   a.part_s = reinterpret_cast<double *>(base + p.off_s);
   a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
   a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g; a.grad_rows = grad_rows;
@@ -813,7 +810,7 @@ DhWs dh_ws(const gto_config *c, int hidden_dim) {
   L.off_list_p = off; off += up(rd * sizeof(int32_t));
   L.off_list_slot = off; off += up(rd * sizeof(int32_t));
   L.off_count = off; off += 256;
-  L.off_s = off; off += up(rd * 64 * sizeof(double));     // at most 64 vocabulary chunks per row
+  L.off_s = off; off += up(rd * 64 * sizeof(double));     // at most 64 partial results per row
   L.off_hi = off; off += up(rd * (size_t)c->V * sizeof(uint16_t));
   L.off_lo = off; off += up(rd * (size_t)c->V * sizeof(uint16_t));
   L.off_partial = off; off += up((size_t)L.n_splits * rd * hidden_dim * sizeof(float));
@@ -867,8 +864,7 @@ int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_c
     gto::FusedArgs a{};
     a.hidden = hidden_cur; a.w = w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = rows_per_root(cfg);
     a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = rd; a.m_dev = count; a.row_list = list_slot; a.out_by_list = 1;
-    a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-    a.xcd_patches = cfg->fused_layout == 0;
+    set_geometry(a, p);
     a.list_p = list_p; a.coef = fwd->coef; a.lse_by_slot = draft_stats_cur->row_lse; a.g = cfg->g;
     a.plane_hi = hi; a.plane_lo = lo; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node;
     a.part_s = reinterpret_cast<double *>(base + L.off_s);
@@ -882,7 +878,10 @@ int gto_ppo_surrogate_bwd_fused_dh(const gto_config *cfg, const gto_tree *tree_c
     a.m_blocks = L.m_blocks; a.h_blocks = L.h_blocks; a.n_splits = L.n_splits; a.slabs_per_split = L.slabs_per_split;
     a.partial = reinterpret_cast<float *>(base + L.off_partial);
     a.part_s = reinterpret_cast<const double *>(base + L.off_s);
-    a.n_chunks = fused_plan(cfg, rd, 1).n_chunks;
+    {
+      const FusedPlan p = fused_plan(cfg, rd, 1);
+      a.n_tiles = p.n_tiles; a.groups = p.groups; a.patch_rows = p.patch_rows; a.patch_cols = p.patch_cols;
+    }
     a.list_p = list_p; a.sel_tok = tree_cur->sel_tok; a.path_node = path_cur->path_node; a.coef = fwd->coef;
     a.dh_rows = dh_rows;
     ProfScope ps("fused_dh", st);
@@ -979,8 +978,7 @@ int gto_token_loss_fwd_fused(const gto_config *cfg, const void *hidden, int32_t 
     gto::FusedArgs a{};
     a.hidden = hidden; a.w = which ? w_target_vh : w_draft_vh; a.hidden_dim = hidden_dim; a.V = cfg->V; a.rho = 1;
     a.d = cfg->d; a.kslots = cfg->k; a.ktop = 1; a.M = cfg->R;
-    a.m_blocks = p.m_blocks; a.n_tiles = p.n_tiles; a.n_chunks = p.n_chunks; a.tiles_per_chunk = p.tiles_per_chunk;
-    a.xcd_patches = cfg->fused_layout == 0;
+    set_geometry(a, p);
     a.store_rows = which ? tl : dl; a.store_pitch = L.pitch;
     ProfScope ps(which ? "fused_root_logits_target" : "fused_root_logits_draft", st);
     gto::launch_fused_rows(a, st);

@@ -109,7 +109,7 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4
   const unsigned char *nS = r.ldsb + s1 * FSTAGE_B;
 #pragma unroll
   for (int idx = 0; idx < 16; ++idx) {
-    const int i = idx >> 2, j = idx & 3;
+    const int i = idx >> 2, j = (i & 1) ? 3 - (idx & 3) : (idx & 3);    // boustrophedon: one operand changes per MFMA
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
     if (idx < 4) {
       fb[1][idx] = *reinterpret_cast<const bf16x8 *>(sS + (r.fb_base ^ 32) + idx * 32 * FROWB);
@@ -135,7 +135,7 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4
   }
 #pragma unroll
   for (int idx = 0; idx < 16; ++idx) {
-    const int i = idx >> 2, j = idx & 3;
+    const int i = idx >> 2, j = (i & 1) ? 3 - (idx & 3) : (idx & 3);
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[1][j], acc[i][j], 0, 0, 0);
     if (NEXT) {
       if (idx < 4) fb[0][idx] = *reinterpret_cast<const bf16x8 *>(nS + r.fb_base + idx * 32 * FROWB);
@@ -198,6 +198,67 @@ __device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds
   slab_step<false, false, false>(acc, fa, fb, r, ap, bp, kt & 3);
 }
 
+// ---- work distribution of the row pass
+// The 256 x 256 output tiles form an (m_blocks x n_tiles) grid; it is cut into patches of pr row blocks x
+// pc column tiles: PR patch rows of QC patches ("patch steps").  The launch has G groups of pr * pc
+// workgroups; workgroup (dr, dc) of a group computes tile (row block P pr + dr, column tile Q pc + dc) of
+// every step (P, Q) its group owns, one after the other.  A group owns
+//   - base = PR / G whole patch rows (group x: rows x base .. (x+1) base - 1), swept left to right, and
+//   - an equal share of the steps of the remaining PR % G patch rows (row-major, contiguous).
+// Consecutive steps of a patch row keep the row block, so a workgroup's 256 rows carry their statistics in
+// registers from tile to tile and write one partial result per (row, group, dc) when a patch row (or the
+// group's share of it) ends.
+//   - Workgroup i of a launch runs on XCD i % 8, so with G = 8 a group is the 32 compute units of one XCD:
+//     at any time its L2 serves pr row-operand streams and pc column-operand streams to pr * pc workgroups.
+//   - While the groups sweep their whole patch rows they all sit at about the same column position, so a
+//     column-operand tile is fetched from HBM by the first group and from the memory-side cache by the others.
+//   - Every group gets the same number of steps to within one, whatever the shape: no tail of idle
+//     compute units, and nothing depends on the row count being known on the host (a launch over a
+//     device-side row list reads its count here).
+struct RowSched {
+  int m_blocks, n_tiles, PR, QC, pr, pc, G;
+  int base;         // whole patch rows per group
+  int64_t Tr;       // steps of the remaining patch rows, shared out evenly
+};
+__device__ __forceinline__ RowSched make_sched(int64_t M, int n_tiles, int G, int pr, int pc) {
+  RowSched s;
+  s.m_blocks = (int)((M + FBM - 1) / FBM);
+  s.n_tiles = n_tiles;
+  s.pr = pr; s.pc = pc; s.G = G;
+  s.PR = (s.m_blocks + pr - 1) / pr;
+  s.QC = (n_tiles + pc - 1) / pc;
+  s.base = s.PR / G;
+  s.Tr = (int64_t)(s.PR - s.base * G) * s.QC;
+  return s;
+}
+__device__ __forceinline__ int64_t rest_begin(const RowSched &s, int x) { return s.Tr * x / s.G; }
+// number of steps of group x, and its i-th step as (patch row, patch column)
+__device__ __forceinline__ int64_t group_steps(const RowSched &s, int x) {
+  return (int64_t)s.base * s.QC + (rest_begin(s, x + 1) - rest_begin(s, x));
+}
+__device__ __forceinline__ void group_step(const RowSched &s, int x, int64_t i, int &P, int &Q) {
+  const int64_t n1 = (int64_t)s.base * s.QC;
+  if (i < n1) {
+    P = x * s.base + (int)(i / s.QC);
+    Q = (int)(i % s.QC);
+  } else {
+    const int64_t r = rest_begin(s, x) + (i - n1);
+    P = s.base * s.G + (int)(r / s.QC);
+    Q = (int)(r % s.QC);
+  }
+}
+// does partial slot (group x, column phase dc) of row block `mblock` hold a result?
+__device__ __forceinline__ bool slot_valid(const RowSched &s, int mblock, int slot) {
+  const int x = slot / s.pc, dc = slot - x * s.pc;
+  if (x >= s.G) return false;
+  const int P = mblock / s.pr;
+  if (P < s.base * s.G) return x == P / s.base && dc < s.n_tiles;
+  const int64_t row_lo = (int64_t)(P - s.base * s.G) * s.QC;
+  const int64_t lo = max(rest_begin(s, x), row_lo), hi = min(rest_begin(s, x + 1), row_lo + s.QC);
+  if (lo >= hi) return false;
+  return (int)(lo - row_lo) * s.pc + dc < s.n_tiles;   // the first tile of the segment exists (later ones lie further right)
+}
+
 enum FusedMode { kFusedStats = 0, kFusedBwd = 1, kFusedPlanes = 2, kFusedStore = 3 };
 
 template <int KT, int MODE>
@@ -207,30 +268,13 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // workgroup -> (row block, vocabulary chunk)
-  int mblock, chunk;
-  {
-    const int id = blockIdx.x;
-    if (a.xcd_patches) {
-      // 32 consecutive workgroups of one XCD form a 4 (row blocks) x 8 (chunks) patch, so that the
-      // XCD's L2 serves 4 A streams and 8 W streams to 32 workgroups
-      const int xcd = id & 7, seq = id >> 3;
-      const int patch = (seq >> 5) * 8 + xcd, within = seq & 31;
-      const int pcs = (a.n_chunks + 7) >> 3;
-      mblock = (patch / pcs) * 4 + (within >> 3);
-      chunk = (patch % pcs) * 8 + (within & 7);
-    } else {
-      mblock = id / a.n_chunks;
-      chunk = id - mblock * a.n_chunks;
-    }
-    if (mblock >= a.m_blocks || chunk >= a.n_chunks) return;
-  }
-  const int tile0 = chunk * a.tiles_per_chunk;
-  const int tile1 = min(tile0 + a.tiles_per_chunk, a.n_tiles);
-  if (tile0 >= tile1) return;
-  const int64_t row0 = (int64_t)mblock * FBM;
   const int64_t M = a.m_dev ? min((int64_t)*a.m_dev, a.M) : a.M;   // row count may live on the device
-  if (row0 >= M) return;
+  const RowSched sc = make_sched(M, a.n_tiles, a.groups, a.patch_rows, a.patch_cols);
+  const int grp = blockIdx.x % sc.G, cell = blockIdx.x / sc.G;       // workgroup (dr, dc) of group grp
+  const int dr = cell / sc.pc, dc = cell - dr * sc.pc;
+  const int slot = grp * sc.pc + dc;                                  // partial-result slot of a row
+  const int n_slots = sc.G * sc.pc;
+  const int64_t n_steps = group_steps(sc, grp);
   const int HD = a.hidden_dim;
   const int kt_count = HD / FBK;
   const uint16_t *__restrict__ Hp = static_cast<const uint16_t *>(a.hidden);
@@ -239,24 +283,13 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   // global -> LDS assignment: one wave instruction fills 16 rows x 64 bytes; wave w issues the
   // row groups 64 w + 16 j (j = 0..3) of both operands.  Lane l lands at row l/4, 16-byte unit
   // l%4 of its group; it fetches the unit (l%4) ^ ((row/4)%4) of that row, so that the fragment
-  // reads below (32 rows at one k unit) spread over all LDS banks.
+  // reads (32 rows at one k unit) spread over all LDS banks.
   const int ld_row = 64 * wave + (lane >> 2);            // + 16 j
   const int ld_unit = (lane & 3) ^ ((lane >> 4) & 3);
-  const uint16_t *a_ptr[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int64_t g = row0 + ld_row + 16 * j;
-    if (g >= M) g = M - 1;
-    const int64_t slot = a.row_list ? (int64_t)a.row_list[g] : used_slot_index(g, a.rho, a.d, a.kslots);
-    a_ptr[j] = Hp + slot * HD + ld_unit * 8;
-  }
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) uint16_t *)lds;
   const unsigned wbase = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)wave * 4096u);
   // the list keeps the KT >= ktop best of the row; its last entry is the insertion threshold
   RowState<KT> st;
-  st.m = neg_inf(); st.c = 0.f; st.s = 0.0;
-#pragma unroll
-  for (int i = 0; i < KT; ++i) { st.v[i] = neg_inf(); st.id[i] = kNoId; }
   const int ktop = a.ktop;
   // backward mode: thread t writes coef * (-softmax) of row t and sums the probabilities of all
   // tokens but the accepted one
@@ -265,24 +298,73 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   float *b_out = nullptr;
   double b_others = 0.0;
   uint16_t *p_hi = nullptr, *p_lo = nullptr;
-  if (MODE == kFusedBwd || MODE == kFusedPlanes) {
-    const int64_t gme = row0 + tid;
-    if (gme < M) {
-      const int pidx = a.list_p[gme];
-      const int rr = pidx / a.d;
-      b_lse = a.lse_by_slot[a.row_list[gme]];
-      b_coef = a.coef[rr];
-      b_tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
-      if (MODE == kFusedBwd) {
-        b_out = a.grad_rows + (int64_t)pidx * a.V;
-      } else {
-        p_hi = a.plane_hi + gme * a.V;
-        p_lo = a.plane_lo + gme * a.V;
+  const uint16_t *a_ptr[4] = {nullptr, nullptr, nullptr, nullptr};
+  int64_t row0 = 0;
+  int cur_P = -1;
+  bool rows_live = false;      // this workgroup's row block of the current patch row exists
+
+  // partial results of the row-block segment that ends (patch row finished, or the group's range did)
+  auto flush = [&]() {
+    const int64_t g = row0 + tid;
+    if (MODE == kFusedStore || g >= M) return;
+    const int64_t pi = g * n_slots + slot;
+    if (MODE == kFusedBwd || MODE == kFusedPlanes) {
+      a.part_s[pi] = b_others;
+      return;
+    }
+    a.part_m[pi] = st.m;
+    a.part_c[pi] = st.c;
+    a.part_s[pi] = st.s;
+#pragma unroll
+    for (int i = 0; i < KT; ++i) {
+      if (i < ktop) {
+        a.part_v[pi * ktop + i] = st.v[i];
+        a.part_i[pi * ktop + i] = st.id[i];
       }
     }
-  }
+  };
 
-  for (int tile = tile0; tile < tile1; ++tile) {
+  for (int64_t step = 0; step < n_steps; ++step) {
+    int P, Q;
+    group_step(sc, grp, step, P, Q);
+    if (P != cur_P) {
+      if (rows_live) flush();
+      cur_P = P;
+      const int mblock = P * sc.pr + dr;
+      rows_live = mblock < sc.m_blocks;
+      row0 = (int64_t)mblock * FBM;
+      st.m = neg_inf(); st.c = 0.f; st.s = 0.0;
+#pragma unroll
+      for (int i = 0; i < KT; ++i) { st.v[i] = neg_inf(); st.id[i] = kNoId; }
+      b_others = 0.0; b_out = nullptr; p_hi = nullptr; p_lo = nullptr; b_tok = -1;
+      if (rows_live) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int64_t g = row0 + ld_row + 16 * j;
+          if (g >= M) g = M - 1;
+          const int64_t hs = a.row_list ? (int64_t)a.row_list[g] : used_slot_index(g, a.rho, a.d, a.kslots);
+          a_ptr[j] = Hp + hs * HD + ld_unit * 8;
+        }
+        if (MODE == kFusedBwd || MODE == kFusedPlanes) {
+          const int64_t gme = row0 + tid;
+          if (gme < M) {
+            const int pidx = a.list_p[gme];
+            const int rr = pidx / a.d;
+            b_lse = a.lse_by_slot[a.row_list[gme]];
+            b_coef = a.coef[rr];
+            b_tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+            if (MODE == kFusedBwd) {
+              b_out = a.grad_rows + (int64_t)pidx * a.V;
+            } else {
+              p_hi = a.plane_hi + gme * a.V;
+              p_lo = a.plane_lo + gme * a.V;
+            }
+          }
+        }
+      }
+    }
+    const int tile = Q * sc.pc + dc;
+    if (!rows_live || tile >= sc.n_tiles) continue;     // uniform over the workgroup
     const int n0 = tile * FBN;
     const uint16_t *b_ptr[4];
 #pragma unroll
@@ -443,64 +525,56 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
     }
   }
 
-  // ---- partial results of this (row, chunk)
-  const int64_t g = row0 + tid;
-  if (MODE == kFusedStore) return;
-  if (MODE == kFusedBwd || MODE == kFusedPlanes) {
-    if (g < M) a.part_s[g * a.n_chunks + chunk] = b_others;
-    return;
-  }
-  if (g < M) {
-    const int64_t pi = g * a.n_chunks + chunk;
-    a.part_m[pi] = st.m;
-    a.part_c[pi] = st.c;
-    a.part_s[pi] = st.s;
-#pragma unroll
-    for (int i = 0; i < KT; ++i) {
-      if (i < ktop) {
-        a.part_v[pi * ktop + i] = st.v[i];
-        a.part_i[pi * ktop + i] = st.id[i];
-      }
-    }
-  }
+  if (rows_live) flush();
 }
 
-// One wave per row: merge the chunk partials into the final statistics.
+// One wave per row: merge the partial results of the row's segments (one lane per slot) into the final
+// statistics.  Which slots hold a result follows from the launch geometry alone (slot_valid).
 __global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
   const int64_t g = blockIdx.x;
-  if (a.m_dev && g >= (int64_t)*a.m_dev) return;
+  const int64_t M = a.m_dev ? min((int64_t)*a.m_dev, a.M) : a.M;
+  if (g >= M) return;
   const int lane = threadIdx.x;
-  const int nc = a.n_chunks, ktop = a.ktop;
+  const int ktop = a.ktop;
+  const RowSched sc = make_sched(M, a.n_tiles, a.groups, a.patch_rows, a.patch_cols);
+  const int n_slots = sc.G * sc.pc;                       // <= 64: one lane per slot
   const int64_t oi = a.row_list ? (a.out_by_list ? g : (int64_t)a.row_list[g])
                                 : used_slot_index(g, a.rho, a.d, a.kslots);
   __shared__ float s_v[64 * FKT];
   __shared__ int s_i[64 * FKT];
+  __shared__ int s_claimed[FKT];
+  const bool valid = lane < n_slots && slot_valid(sc, (int)(g / FBM), lane);
   float m = neg_inf(), c = neg_inf();
   double s = 0.0;
-  if (lane < nc) {
-    m = a.part_m[g * nc + lane];
+  if (valid) {
+    m = a.part_m[g * n_slots + lane];
     if (m != neg_inf()) {
-      c = a.part_c[g * nc + lane];
-      s = a.part_s[g * nc + lane];
+      c = a.part_c[g * n_slots + lane];
+      s = a.part_s[g * n_slots + lane];
     }
   }
-  const float M = wave_max(m);
+  const float Mx = wave_max(m);
   const float C = wave_max(c);
   const double S = wave_sum((m == neg_inf()) ? 0.0 : s * (double)__builtin_amdgcn_exp2f(c - C));
-  const double lse = (double)M + kLn2 * (((double)C - (double)M * (double)kLog2e) + log2(S));
+  const double lse = (double)Mx + kLn2 * (((double)C - (double)Mx * (double)kLog2e) + log2(S));
   if (lane == 0) {
-    if (a.row_max) a.row_max[oi] = M;
+    if (a.row_max) a.row_max[oi] = Mx;
     a.row_lse[oi] = (float)lse;
   }
   if (a.top_tok == nullptr) return;
-  const int total = nc * ktop;
-  __shared__ int s_claimed[FKT];
+  // the valid slots' lists, packed: slot j of the packed order is the j-th valid lane
+  const uint64_t vmask = __builtin_amdgcn_ballot_w64(valid);
+  const int n_valid = __builtin_popcountll(vmask);
+  const int my_pos = __builtin_popcountll(vmask & ((1ull << lane) - 1ull));
   if (lane < FKT) s_claimed[lane] = 0;
-  for (int j = lane; j < total; j += 64) {
-    s_v[j] = a.part_v[g * total + j];
-    s_i[j] = a.part_i[g * total + j];
+  if (valid) {
+    for (int i = 0; i < ktop; ++i) {
+      s_v[my_pos * ktop + i] = a.part_v[(g * n_slots + lane) * ktop + i];
+      s_i[my_pos * ktop + i] = a.part_i[(g * n_slots + lane) * ktop + i];
+    }
   }
   __syncthreads();
+  const int total = n_valid * ktop;
   for (int j = lane; j < total; j += 64) {
     const float v = s_v[j];
     const int id = s_i[j];
@@ -523,14 +597,22 @@ __global__ __launch_bounds__(64) void k_fused_merge(FusedArgs a) {
   }
 }
 
+// sum, over the valid slots of row g in slot order, of the per-segment sums of the non-token probabilities
+__device__ __forceinline__ double sum_others(const double *part_s, int64_t g, const RowSched &sc) {
+  const int n_slots = sc.G * sc.pc;
+  double tot = 0.0;
+  for (int c = 0; c < n_slots; ++c)
+    if (slot_valid(sc, (int)(g / FBM), c)) tot += part_s[g * n_slots + c];
+  return tot;
+}
+
 // Backward fix-up, one thread per processed row: the accepted token's entry is coef times the sum
 // of all other probabilities (summed over the vocabulary chunks in a fixed order).
 __global__ void k_fused_bwd_fixup(FusedArgs a) {
   const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t M = a.m_dev ? min((int64_t)*a.m_dev, a.M) : a.M;
   if (g >= M) return;
-  double tot = 0.0;
-  for (int c = 0; c < a.n_chunks; ++c) tot += a.part_s[g * a.n_chunks + c];
+  const double tot = sum_others(a.part_s, g, make_sched(M, a.n_tiles, a.groups, a.patch_rows, a.patch_cols));
   const int pidx = a.list_p[g];
   const int rr = pidx / a.d;
   const int tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
@@ -722,8 +804,9 @@ __global__ __launch_bounds__(256) void k_fused_dh_reduce(FusedDhArgs a) {
   const int tok = min(max(a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]], 0), a.V - 1);
   const float coef = a.coef[rr];
   const uint16_t *wrow = static_cast<const uint16_t *>(a.w_vh) + (int64_t)tok * a.hidden_dim;
-  double others = 0.0;                       // sum of the probabilities of all tokens but the accepted one
-  for (int c = 0; c < a.n_chunks; ++c) others += a.part_s[g * a.n_chunks + c];
+  // sum of the probabilities of all tokens but the accepted one, from the plane pass's segments
+  const int64_t M = min((int64_t)*a.m_dev, a.M);
+  const double others = sum_others(a.part_s, g, make_sched(M, a.n_tiles, a.groups, a.patch_rows, a.patch_cols));
   const float ctok = (float)((double)coef * others);
   for (int h = threadIdx.x; h < a.hidden_dim; h += 256) {
     float sum = 0.f;
@@ -738,11 +821,7 @@ static void set_lds_attr(K kern) {
                             (int)kFusedLdsBytes);
 }
 
-static int fused_grid(const FusedArgs &a) {
-  if (!a.xcd_patches) return a.m_blocks * a.n_chunks;
-  const int pms = (a.m_blocks + 3) / 4, pcs = (a.n_chunks + 7) / 8;
-  return ((pms * pcs + 7) / 8) * 8 * 32;
-}
+static int fused_grid(const FusedArgs &a) { return a.groups * a.patch_rows * a.patch_cols; }
 
 // the kernels that use the whole slab ring need the dynamic LDS limit raised once per process
 // (initialisation of a function-local static is thread-safe)

@@ -91,11 +91,13 @@ struct FusedArgs {
   const int32_t *m_dev;      // optional: actual row count in device memory (<= M)
   const int32_t *row_list;   // optional: slot index of each processed row
   int out_by_list;           // with row_list: statistics are written at the list position, not at the slot
-  int m_blocks, n_tiles, n_chunks, tiles_per_chunk, xcd_patches;
-  float *part_m, *part_c;    // [M, n_chunks]
-  double *part_s;            // [M, n_chunks]
-  float *part_v;             // [M, n_chunks, ktop]
-  int32_t *part_i;           // [M, n_chunks, ktop]
+  int n_tiles;               // column tiles of 256 tokens
+  int groups, patch_rows, patch_cols;   // launch geometry: groups x (patch_rows x patch_cols) workgroups;
+                             // n_slots = groups * patch_cols partial results per row (<= 64)
+  float *part_m, *part_c;    // [M, n_slots]
+  double *part_s;            // [M, n_slots]
+  float *part_v;             // [M, n_slots, ktop]
+  int32_t *part_i;           // [M, n_slots, ktop]
   float *row_max, *row_lse;  // final statistics (row_max may be null)
   int32_t *top_tok;          // may be null
   float *top_logp, *top_logit;  // may be null
@@ -123,8 +125,8 @@ struct FusedDhArgs {
   const int32_t *m_dev;      // actual row count
   int m_blocks, h_blocks, n_splits, slabs_per_split;
   float *partial;            // [n_splits, M, hidden_dim]
-  const double *part_s;      // [M, n_chunks] sum of the non-token probabilities per vocabulary chunk of the plane pass
-  int n_chunks;
+  const double *part_s;      // [M, n_slots] sum of the non-token probabilities per segment of the plane pass
+  int n_tiles, groups, patch_rows, patch_cols;   // geometry of the plane pass (which slots hold a result)
   const int32_t *list_p, *sel_tok, *path_node;
   const float *coef;
   float *dh_rows;            // [R, d, hidden_dim]

@@ -73,10 +73,10 @@ class GtoFusedPath:
 
     def __init__(self, *, R, d, k, g, V, hidden, group_size, device, eta=1.0, eps=0.2, delta=1e-6,
                  grad_scale=1.0, reward_mode=B.GTO_REWARD_LSE, flags=0, want_grad=True, path_mode=0, want_dh=False,
-                 fused_chunks=0, fused_layout=0):
+                 fused_groups=0, fused_layout=0):
         self.cfg = B.make_config(R=R, d=d, k=k, g=g, V=V, dtype=B.GTO_BF16, group_size=group_size,
                                  reward_mode=reward_mode, eta=eta, eps=eps, delta=delta, grad_scale=grad_scale,
-                                 flags=flags, path_mode=path_mode, fused_chunks=fused_chunks,
+                                 flags=flags, path_mode=path_mode, fused_groups=fused_groups,
                                  fused_layout=fused_layout)
         self.hidden = hidden
         self.want_grad = want_grad

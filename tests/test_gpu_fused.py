@@ -36,10 +36,10 @@ def _oracle_logits(t, roots):
     return out
 
 
-def _run(w, t, device, flags=0, fused_chunks=0, fused_layout=0):
+def _run(w, t, device, flags=0, fused_groups=0, fused_layout=0):
     path = GtoFusedPath(R=t["H_cur"].shape[0], d=w.d, k=w.k, g=w.g, V=w.V, hidden=w.hidden, group_size=w.m,
                         device=device, eta=w.eta, eps=w.eps, delta=w.delta, grad_scale=0.5, flags=flags,
-                        fused_chunks=fused_chunks, fused_layout=fused_layout)
+                        fused_groups=fused_groups, fused_layout=fused_layout)
     if flags == 0:
         path.grad_rows.fill_(7.0)
     path.step(t["H_cur"], t["H_ref"], t["W_draft"], t["W_target"])
@@ -115,7 +115,7 @@ def test_fused_row_statistics_when_the_maximum_moves_far(gpu_device, nc):
     W = b[:, None].expand(V, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
     scale = torch.tensor([1.0, -1.0, 0.5, -0.5, 2.0, 0.25])
     H = scale[:, None, None, None].expand(R, d, k, hidden).to(torch.bfloat16).contiguous().to(gpu_device)
-    cfg = G.make_config(R=R, d=d, k=k, g=4, V=V, dtype=torch.bfloat16, fused_chunks=nc)
+    cfg = G.make_config(R=R, d=d, k=k, g=4, V=V, dtype=torch.bfloat16, fused_groups=nc)
     ws = torch.empty(G.gto_fused_workspace_bytes(cfg, hidden), dtype=torch.uint8, device=gpu_device)
     ds, ts = G.alloc_draft_stats(cfg, gpu_device), G.alloc_target_stats(cfg, gpu_device)
     G.gto_fused_draft_row_stats(cfg, H, W, ds, ws)
@@ -252,13 +252,13 @@ def test_fused_step_can_be_captured_in_a_hip_graph(gpu_device):
 
 
 def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
-    _say("fused: chunk count / workgroup layout invariance")
+    _say("fused: launch geometry (groups, patch shape) invariance")
     w = S.FusedWorkload("case", R=24, V=4096, k=8, d=3, g=20, m=8, hidden=256, h_scale=3.0, w_sigma=0.05,
                         w_corr=0.9, ref_sigma=0.05)
     t = S.make_fused(w, gpu_device)
     ref = _run(w, t, gpu_device)
-    for nc, layout in ((1, 1), (3, 0), (16, 0)):
-        other = _run(w, t, gpu_device, fused_chunks=nc, fused_layout=layout)
+    for nc, layout in ((1, 1), (3, 0), (8, 1), (16, 1)):
+        other = _run(w, t, gpu_device, fused_groups=nc, fused_layout=layout)
         for tag in ("cur", "ref"):
             for grp in ("tree", "reward"):
                 for n, x in ref.buf[tag][grp].items():

@@ -76,6 +76,6 @@ def test_random_shapes_fused(gpu_device):
         nc = rng.choice([0, 1, 3])
         T._say(f"random fused shape {it}: R={R} d={d} k={k} g={g} m={m} hidden={hidden} V={V} corr={corr} chunks={nc}")
         t = S.make_fused(w, gpu_device)
-        path = F._run(w, t, gpu_device, fused_chunks=nc)
+        path = F._run(w, t, gpu_device, fused_groups=nc)
         L, _ = F._compare_fused(w, t, path, list(range(R)))
         T._compare_ppo(w, L, path)

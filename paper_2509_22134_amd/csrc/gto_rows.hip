@@ -274,6 +274,35 @@ __global__ __launch_bounds__(WAVES *kWave) void k_row_stats(RowStatsArgs a) {
   }
 }
 
+// Four consecutive elements of a row, at element index 4 * q4, as fp32: one 8-byte (bf16) or 16-byte (fp32)
+// nontemporal load.  A wave's 64 such loads are contiguous, and so are the 64 16-byte stores of the four
+// fp32 results: every store instruction fills whole cache lines (two 16-byte stores per lane, 32 bytes
+// apart between lanes, leave every line half written and cost ~1.7x the write traffic, measured).
+template <typename T>
+__device__ __forceinline__ void load4(const T *row, int q4, float *x);
+template <>
+__device__ __forceinline__ void load4<uint16_t>(const uint16_t *row, int q4, float *x) {
+  const u32x2 q = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(row) + q4);
+  x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
+  x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
+}
+template <>
+__device__ __forceinline__ void load4<float>(const float *row, int q4, float *x) {
+  const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + q4);
+  x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+}
+// N consecutive elements at element index N * idx: N == 4 as above; N == the elements of a 16-byte
+// vector for kernels that only read (16-byte loads stream ~20 % faster than 8-byte ones, measured).
+template <typename T, int N>
+__device__ __forceinline__ void load_group(const T *row, int idx, float *x) {
+  if constexpr (N == 4) {
+    load4<T>(row, idx, x);
+  } else {
+    static_assert(N == Elem<T>::kPerVec, "group is four elements or one 16-byte vector");
+    Elem<T>::unpack(__builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + idx), x);
+  }
+}
+
 // ------------------------------------------------------------------------------- backward
 // One workgroup of 16 waves per (root, step): only the few hundred rows on accepted paths do any work,
 // so the parallelism has to come from inside the row.
@@ -308,32 +337,33 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
   float others = 0.f;
   bool own_tok = false;
   if (VEC) {
-    // four elements per lane per step: one 8- or 16-byte load, one 16-byte store
+    // groups of four elements, kBwdUnroll groups in flight per lane: only a few hundred rows carry a
+    // gradient, so the bytes in flight have to come from inside a row
+    constexpr int kBwdUnroll = 4;
     const int n4 = V / 4;
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-      float x[4];
-      if (sizeof(T) == 2) {
-        const u32x2 q = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(row) + i);
-        x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
-        x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
-      } else {
-        const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + i);
-        x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
-        x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
-      }
-      float gq[4];
-      float part = 0.f;
+    for (int i0 = threadIdx.x; i0 < n4; i0 += kBwdUnroll * kBwdThreads) {
+      float x[kBwdUnroll][4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float p = __builtin_amdgcn_exp2f((x[e] - lse) * kLog2e);
-        gq[e] = -coef * p;
-        const bool is_tok = (i * 4 + e == tok);
-        own_tok = own_tok || is_tok;
-        part += is_tok ? 0.f : p;
+      for (int u = 0; u < kBwdUnroll; ++u)
+        if (i0 + u * kBwdThreads < n4) load4<T>(row, i0 + u * kBwdThreads, x[u]);
+#pragma unroll
+      for (int u = 0; u < kBwdUnroll; ++u) {
+        const int i = i0 + u * kBwdThreads;
+        if (i >= n4) continue;
+        float gq[4];
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = __builtin_amdgcn_exp2f((x[u][e] - lse) * kLog2e);
+          gq[e] = -coef * p;
+          const bool is_tok = (i * 4 + e == tok);
+          own_tok = own_tok || is_tok;
+          part += is_tok ? 0.f : p;
+        }
+        others += part;
+        const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
       }
-      others += part;
-      const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
-      __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
     }
   } else {
     for (int i = threadIdx.x; i < V; i += blockDim.x) {
@@ -358,73 +388,67 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
 
 // ------------------------------------------------------------------------------- token-level loss
 // One workgroup per root: streams the root rows (slot (0,0)) of the draft and the target logits
-// together with 16-byte loads, two vectors of each row in flight per lane.  Forward:
-// H = lse_M - sum_v p_T(v) d_v.  Backward: scale * (p_M - p_T) as an fp32 row (16-byte stores when the
-// output rows are 16-byte aligned).  The last vector of a row may reach past V: it stays inside the
-// row's storage (row pitches are multiples of 16 bytes) and the surplus elements are masked.
+// together.  Forward: H = lse_M - sum_v p_T(v) d_v.  Backward: scale * (p_M - p_T) as an fp32 row.
 constexpr int kTokThreads = 256;
-template <typename T, bool BWD, bool VEC_ST>
+template <typename T, bool BWD, bool VEC>
 __global__ __launch_bounds__(kTokThreads) void k_token_loss(TokenLossArgs a) {
-  constexpr int EPV = Elem<T>::kPerVec;
   const int r = blockIdx.x;
   const float w = a.weight ? a.weight[r] : 1.f;
   const int64_t si = stat_index(r, 0, 0, a.d, a.k);
   const int64_t lo = a.root_stride ? (int64_t)r * a.root_stride : si * a.row_stride;
-  const u32x4 *__restrict__ dvec = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.draft_logits) + lo);
-  const u32x4 *__restrict__ tvec = reinterpret_cast<const u32x4 *>(static_cast<const T *>(a.target_logits) + lo);
+  const T *__restrict__ drow = static_cast<const T *>(a.draft_logits) + lo;
+  const T *__restrict__ trow = static_cast<const T *>(a.target_logits) + lo;
   const float d_lse = a.d_lse[si], t_lse = a.t_lse[si];
   const int V = a.V;
-  const int nvec = (V + EPV - 1) / EPV;
   float *__restrict__ out = BWD ? a.grad + (int64_t)r * V : nullptr;
   const float scale = BWD ? a.grad_scale * w * a.inv_count[0] : 0.f;
   double acc = 0.0;
-  for (int i0 = threadIdx.x; i0 < nvec; i0 += 2 * kTokThreads) {
-    u32x4 qd[2], qt[2];
+  // Groups of kGroup elements, kUnroll groups of each row in flight per lane.  The backward takes
+  // groups of four so that its stores fill whole lines (see load4); the forward, which stores nothing,
+  // takes whole 16-byte vectors.  VEC: V % kGroup == 0 and, for the backward, 16-byte aligned output
+  // rows; otherwise one element at a time.
+  constexpr int kGroup = BWD ? 4 : Elem<T>::kPerVec;
+  constexpr int kUnroll = BWD ? 4 : 2;
+  const int n4 = VEC ? V / kGroup : 0;
+  for (int i0 = threadIdx.x; i0 < n4; i0 += kUnroll * kTokThreads) {
+    float xd[kUnroll][kGroup], xt[kUnroll][kGroup];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int i = i0 + h * kTokThreads;
-      if (i < nvec) {
-        qd[h] = __builtin_nontemporal_load(dvec + i);
-        qt[h] = __builtin_nontemporal_load(tvec + i);
+    for (int u = 0; u < kUnroll; ++u)
+      if (i0 + u * kTokThreads < n4) {
+        load_group<T, kGroup>(drow, i0 + u * kTokThreads, xd[u]);
+        load_group<T, kGroup>(trow, i0 + u * kTokThreads, xt[u]);
       }
-    }
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int i = i0 + h * kTokThreads;
-      if (i >= nvec) continue;
-      float xd[EPV], xt[EPV];
-      Elem<T>::unpack(qd[h], xd);
-      Elem<T>::unpack(qt[h], xt);
-      if (BWD) {
-        float gq[EPV];
+    for (int u = 0; u < kUnroll; ++u) {
+      const int i = i0 + u * kTokThreads;
+      if (i >= n4) continue;
+      if constexpr (BWD) {
+        float gq[4];
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) {
-          const float pm = __builtin_amdgcn_exp2f((xd[e] - d_lse) * kLog2e);
-          const float pt = __builtin_amdgcn_exp2f((xt[e] - t_lse) * kLog2e);
+        for (int e = 0; e < 4; ++e) {
+          const float pm = __builtin_amdgcn_exp2f((xd[u][e] - d_lse) * kLog2e);
+          const float pt = __builtin_amdgcn_exp2f((xt[u][e] - t_lse) * kLog2e);
           gq[e] = scale * (pm - pt);
         }
-#pragma unroll
-        for (int q4 = 0; q4 < EPV / 4; ++q4) {
-          const int e0 = i * EPV + q4 * 4;
-          if (VEC_ST && e0 + 3 < V) {
-            const f32x4 o = {gq[q4 * 4], gq[q4 * 4 + 1], gq[q4 * 4 + 2], gq[q4 * 4 + 3]};
-            __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out + e0));
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (e0 + e < V) out[e0 + e] = gq[q4 * 4 + e];
-          }
-        }
+        const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
       } else {
         float part = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) {
-          const float pt = __builtin_amdgcn_exp2f((xt[e] - t_lse) * kLog2e);
-          const float term = (pt > 0.f) ? pt * (xd[e] - d_lse) : 0.f;      // 0 * log 0 := 0
-          part += (i * EPV + e < V) ? term : 0.f;
+        for (int e = 0; e < kGroup; ++e) {
+          const float pt = __builtin_amdgcn_exp2f((xt[u][e] - t_lse) * kLog2e);
+          part += (pt > 0.f) ? pt * (xd[u][e] - d_lse) : 0.f;      // 0 * log 0 := 0
         }
         acc += (double)part;
       }
+    }
+  }
+  if (!VEC) {
+    for (int i = threadIdx.x; i < V; i += kTokThreads) {
+      const float dv = Elem<T>::load1(drow + i), tv = Elem<T>::load1(trow + i);
+      const float pt = __builtin_amdgcn_exp2f((tv - t_lse) * kLog2e);
+      if (BWD) out[i] = scale * (__builtin_amdgcn_exp2f((dv - d_lse) * kLog2e) - pt);
+      else acc += (double)((pt > 0.f) ? pt * (dv - d_lse) : 0.f);
     }
   }
   if (BWD) return;
@@ -465,8 +489,10 @@ __global__ __launch_bounds__(256) void k_token_loss_mean(TokenLossArgs a) {
 
 void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t st) {
   const dim3 grid(a.R), block(kTokThreads);
+  // rows start 16-byte aligned; the backward walks groups of four elements, the forward 16-byte vectors
+  const int group = bwd ? 4 : (dtype == 0 ? 8 : 4);
+  const bool vec = (a.V % group == 0) && (!bwd || (reinterpret_cast<uintptr_t>(a.grad) & 15) == 0);
   if (bwd) {
-    const bool vec = (a.V % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.grad) & 15) == 0);
     if (dtype == 0) {
       if (vec) hipLaunchKernelGGL((k_token_loss<uint16_t, true, true>), grid, block, 0, st, a);
       else hipLaunchKernelGGL((k_token_loss<uint16_t, true, false>), grid, block, 0, st, a);
@@ -476,8 +502,13 @@ void launch_token_loss(const TokenLossArgs &a, int dtype, bool bwd, hipStream_t 
     }
     return;
   }
-  if (dtype == 0) hipLaunchKernelGGL((k_token_loss<uint16_t, false, false>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((k_token_loss<float, false, false>), grid, block, 0, st, a);
+  if (dtype == 0) {
+    if (vec) hipLaunchKernelGGL((k_token_loss<uint16_t, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_token_loss<uint16_t, false, false>), grid, block, 0, st, a);
+  } else {
+    if (vec) hipLaunchKernelGGL((k_token_loss<float, false, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((k_token_loss<float, false, false>), grid, block, 0, st, a);
+  }
   hipLaunchKernelGGL(k_token_loss_mean, dim3(1), dim3(256), 0, st, a);
 }
 

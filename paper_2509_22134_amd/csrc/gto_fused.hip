@@ -26,18 +26,21 @@ constexpr int FROWB = FBK * 2;                     // bytes per staged row (bf16
 constexpr int FSTAGE_B = (FBM + FBN) * FROWB;      // bytes per stage: 256 hidden rows, then 256 W rows
 constexpr int FNST = 4;                            // LDS stages: one being multiplied, FNST-1 landing (3 and 5 measured slower)
 constexpr int FKT = 16;                            // capacity of the per-thread top list
-constexpr int FSTG_LD = 65;                        // staging row stride (floats)
+constexpr int FSTG_LD = 65;                        // staging row stride (floats), row-major staging
+constexpr int FSTG_CM = FBM + 4;                   // staging column stride (floats), column-major staging
 constexpr size_t kFusedLdsBytes = (size_t)FNST * FSTAGE_B;
 static_assert(kFusedLdsBytes >= (size_t)FBM * FSTG_LD * sizeof(float), "staging area must fit");
+static_assert(kFusedLdsBytes >= (size_t)64 * FSTG_CM * sizeof(float), "staging area must fit");
+static_assert(63 * FSTG_CM * sizeof(float) < 65536, "a row's 64 staged columns are reached with immediate offsets");
 static_assert(FNST == 4, "the wait counts and the issue order of the main loop are written for this ring");
 
 // wait until at most n of this wave's vector memory operations are outstanding (n known at compile time)
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N == 0 || N == 8 || N == 12, "counts used by the slab ring");
+  static_assert(N == 0 || N == 8 || N == 16, "counts used by the slab ring");
   if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  if (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l of the wave lands at lds_addr + 16 l
@@ -90,21 +93,24 @@ __device__ __forceinline__ void list_insert(float (&v)[KT], int (&id)[KT], float
 // followed by at most one memory instruction (pinned by scheduling barriers), which issues while the
 // MFMA executes.  One slab:
 //   first half  (k units 0, 1): after MFMA 0..7 the fragment reads of the second half (the four W
-//               fragments first: its first MFMA row needs them all); after MFMA 8..11 the W loads of slab
-//               s+2; then the wait until slab s+1 has landed, and the barrier
-//   second half (k units 2, 3): after MFMA 0..7 the first-half fragments of slab s+1; after MFMA 8..11
-//               the hidden-state loads of slab s+3
+//               fragments first: its first MFMA row needs them all); then the wait until slab s+1 has
+//               landed, and the barrier
+//   second half (k units 2, 3): after MFMA 0..7 the first-half fragments of slab s+1; after MFMA 8..15
+//               the loads of slab s+3 (hidden states, then W): a slab is requested two and a half slabs
+//               (about 5000 clocks) before its first use, which is what a miss in the L2 needs here
 struct SlabRing {
   unsigned wbase;              // LDS byte address of this wave's 4 KB landing area inside stage 0
   const unsigned char *ldsb;   // the ring
   int fa_base, fb_base;        // this lane's fragment byte offsets inside a stage (k units 0 / 1)
 };
 
-template <bool LB, bool LA, bool NEXT>
+// LOAD3: slab s+3 exists and is requested here.  PEND2: slab s+2 exists (its 8 loads are in flight at the
+// wait).  NEXT: slab s+1 exists.
+template <bool LOAD3, bool PEND2, bool NEXT>
 __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
                                           const SlabRing &r, const uint16_t *(&ap)[4], const uint16_t *(&bp)[4],
                                           int stage) {
-  const int s1 = (stage + 1) % FNST, s2 = (stage + 2) % FNST, s3 = (stage + 3) % FNST;
+  const int s1 = (stage + 1) % FNST, s3 = (stage + 3) % FNST;
   const unsigned char *sS = r.ldsb + stage * FSTAGE_B;
   const unsigned char *nS = r.ldsb + s1 * FSTAGE_B;
 #pragma unroll
@@ -115,20 +121,14 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4
       fb[1][idx] = *reinterpret_cast<const bf16x8 *>(sS + (r.fb_base ^ 32) + idx * 32 * FROWB);
     } else if (idx < 8) {
       fa[1][idx - 4] = *reinterpret_cast<const bf16x8 *>(sS + (r.fa_base ^ 32) + (idx - 4) * 32 * FROWB);
-    } else if (idx < 12) {
-      // stage s+2 was last read as slab s-2: every wave passed the barrier of slab s-1 after that
-      if (LB) {
-        load_to_lds16(r.wbase + s2 * FSTAGE_B + FBM * FROWB + (idx - 8) * 1024, bp[idx - 8]);
-        bp[idx - 8] += FBK;
-      }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
   if (NEXT) {
     // this wave's share of slab s+1 has landed when at most the 8 loads of slab s+2 are still out; the
     // barrier extends that to the other waves' shares, and tells that every wave is past its reads of
-    // slab s-1, whose stage the next loads overwrite
-    if (LB) wait_vmcnt<8>();
+    // slab s-1, whose stage the loads below overwrite
+    if (PEND2) wait_vmcnt<8>();
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -141,10 +141,13 @@ __device__ __forceinline__ void slab_step(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4
       if (idx < 4) fb[0][idx] = *reinterpret_cast<const bf16x8 *>(nS + r.fb_base + idx * 32 * FROWB);
       else if (idx < 8) fa[0][idx - 4] = *reinterpret_cast<const bf16x8 *>(nS + r.fa_base + (idx - 4) * 32 * FROWB);
     }
-    if (idx >= 8 && idx < 12) {
-      if (LA) {
+    if (LOAD3) {
+      if (idx >= 8 && idx < 12) {
         load_to_lds16(r.wbase + s3 * FSTAGE_B + (idx - 8) * 1024, ap[idx - 8]);
         ap[idx - 8] += FBK;
+      } else if (idx >= 12) {
+        load_to_lds16(r.wbase + s3 * FSTAGE_B + FBM * FROWB + (idx - 12) * 1024, bp[idx - 12]);
+        bp[idx - 12] += FBK;
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -167,22 +170,19 @@ __device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds
   r.fa_base = (wm * 128 + (lane & 31)) * FROWB + fsw;
   r.fb_base = (FBM + wn * 128 + (lane & 31)) * FROWB + fsw;
   __syncthreads();                           // the previous user of the ring (an epilogue's staging area) is done
-  // prologue: slabs 0 and 1 and the hidden-state half of slab 2 (its W half follows in the loop)
+  // prologue: slabs 0, 1 and 2
 #pragma unroll
-  for (int s_ = 0; s_ < 2; ++s_)
+  for (int s_ = 0; s_ < 3; ++s_)
     if (s_ < kt_count) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + s_ * FSTAGE_B + j * 1024, ap[j]); ap[j] += FBK; }
 #pragma unroll
       for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + s_ * FSTAGE_B + FBM * FROWB + j * 1024, bp[j]); bp[j] += FBK; }
     }
-  if (2 < kt_count) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) { load_to_lds16(wbase + 2 * FSTAGE_B + j * 1024, ap[j]); ap[j] += FBK; }
-    wait_vmcnt<12>();                        // slab 0 landed; slab 1 and half of slab 2 in flight
-  } else {
-    wait_vmcnt<0>();
-  }
+  // slab 0 landed; the later ones stay in flight
+  if (kt_count > 2) wait_vmcnt<16>();
+  else if (kt_count > 1) wait_vmcnt<8>();
+  else wait_vmcnt<0>();
   __syncthreads();
   bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
@@ -190,10 +190,10 @@ __device__ __forceinline__ void tile_mainloop(f32x16 (&acc)[4][4], uint16_t *lds
     fa[0][t] = *reinterpret_cast<const bf16x8 *>(r.ldsb + r.fa_base + t * 32 * FROWB);
     fb[0][t] = *reinterpret_cast<const bf16x8 *>(r.ldsb + r.fb_base + t * 32 * FROWB);
   }
-  // slabs whose three successors exist run with every load enabled; the last three drop them one by one
+  // slabs whose third successor exists request it; the last three request nothing
   int kt = 0;
   for (; kt + 3 < kt_count; ++kt) slab_step<true, true, true>(acc, fa, fb, r, ap, bp, kt & 3);
-  if (kt + 2 < kt_count) { slab_step<true, false, true>(acc, fa, fb, r, ap, bp, kt & 3); ++kt; }
+  if (kt + 2 < kt_count) { slab_step<false, true, true>(acc, fa, fb, r, ap, bp, kt & 3); ++kt; }
   if (kt + 1 < kt_count) { slab_step<false, false, true>(acc, fa, fb, r, ap, bp, kt & 3); ++kt; }
   slab_step<false, false, false>(acc, fa, fb, r, ap, bp, kt & 3);
 }
@@ -389,8 +389,102 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
     }
     __syncthreads();                           // all fragment reads done before the staging area is written
 
-    // ---- epilogue: four 64-column quarters through the staging area; thread t owns row t
     float *stg = reinterpret_cast<float *>(lds);
+    if constexpr (MODE == kFusedStats) {
+      // ---- epilogue of the statistics pass: thread t owns row t.  Four phases; phase nt takes column
+      // tile nt of both wave columns (64 columns, every wave takes part) through a column-major staging
+      // area: the four consecutive rows a lane holds of a column leave as one 16-byte write (16 writes
+      // per wave and phase, conflict-free with the column stride FSTG_CM), and a thread then reads its
+      // row with one 4-byte read per column, all 64 issued back to back.
+      const bool full_tile = (n0 + FBN <= a.V);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        {
+          float *wcol = stg + (wn * 32 + (lane & 31)) * FSTG_CM + wm * 128 + 4 * (lane >> 5);
+#pragma unroll
+          for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+              const f32x4 q = {acc[mt][nt][4 * g4], acc[mt][nt][4 * g4 + 1], acc[mt][nt][4 * g4 + 2],
+                               acc[mt][nt][4 * g4 + 3]};
+              *reinterpret_cast<f32x4 *>(wcol + mt * 32 + 8 * g4) = q;
+            }
+            __builtin_amdgcn_sched_barrier(0);   // 16 accumulator reads at a time keep the register pressure low
+          }
+        }
+        __syncthreads();
+        // staged column c is vocabulary entry n0 + 128 (c / 32) + 32 nt + c % 32
+        const int cid0 = n0 + nt * 32;
+        float x[64];
+#pragma unroll
+        for (int c = 0; c < 64; ++c) x[c] = stg[c * FSTG_CM + tid];
+        if (!full_tile) {
+#pragma unroll
+          for (int c = 0; c < 64; ++c)
+            if (cid0 + (c >> 5) * 128 + (c & 31) >= a.V) x[c] = neg_inf();     // adds nothing to max and sum
+        }
+        // One pass over the 64 new logits: maximum and sum of exp2 against the reference exponent the
+        // row already has (st.c, at most 2 below its maximum in the log2 domain).  The sum is
+        // re-referenced when the maximum has moved more than that above st.c, and recomputed in the rare
+        // case that the old reference could have overflowed (or when the row has none yet).
+        const bool have_ref = (st.m != neg_inf());
+        const float c_ref = have_ref ? st.c : 0.f;
+        float cm = neg_inf(), p = 0.f;
+#pragma unroll
+        for (int c = 0; c < 64; ++c) {
+          cm = fmaxf(cm, x[c]);
+          p += __builtin_amdgcn_exp2f(__builtin_fmaf(x[c], kLog2e, -c_ref));
+        }
+        // top-k insertions.  Some row of the workgroup reaches its threshold in almost every phase, and
+        // the other waves wait for that wave at the barrier, so the search for the candidates must not walk
+        // the 64 columns one by one: a row first marks, from registers, the columns that reach the threshold
+        // it had on entry (later thresholds are higher), then visits only those (typically one or two).
+        if (cm >= st.v[KT - 1]) {
+          const float thr = st.v[KT - 1];
+          uint32_t mask_lo = 0, mask_hi = 0;
+#pragma unroll
+          for (int c = 0; c < 32; ++c) {
+            mask_lo |= (x[c] >= thr) ? (1u << c) : 0u;
+            mask_hi |= (x[c + 32] >= thr) ? (1u << c) : 0u;
+          }
+          if (!full_tile) {      // masked columns hold -inf, which reaches the threshold of a list that is not full yet
+            const int left = a.V - cid0;                      // valid columns from cid0 on (low half), from cid0 + 128 (high half)
+            mask_lo &= (left >= 32) ? ~0u : (left <= 0 ? 0u : (1u << left) - 1u);
+            const int left_hi = left - 128;
+            mask_hi &= (left_hi >= 32) ? ~0u : (left_hi <= 0 ? 0u : (1u << left_hi) - 1u);
+          }
+          while ((mask_lo | mask_hi) != 0u) {
+            int c;
+            if (mask_lo != 0u) { c = __builtin_ctz(mask_lo); mask_lo &= mask_lo - 1u; }
+            else { c = 32 + __builtin_ctz(mask_hi); mask_hi &= mask_hi - 1u; }
+            const float xv = stg[c * FSTG_CM + tid];
+            const int xi = cid0 + (c >> 5) * 128 + (c & 31);
+            if (better(xv, xi, st.v[KT - 1], st.id[KT - 1])) list_insert<KT>(st.v, st.id, xv, xi);
+          }
+        }
+        const float m_new = fmaxf(st.m, cm);
+        const float over = __builtin_fmaf(cm, kLog2e, -c_ref);     // how far the new maximum is above the reference
+        if (!have_ref || over > 100.f) {
+          const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
+          float p2 = 0.f;
+#pragma unroll
+          for (int c = 0; c < 64; ++c) p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[c], kLog2e, -c_new));
+          const double s = have_ref ? st.s * (double)__builtin_amdgcn_exp2f(st.c - c_new) : 0.0;
+          st.s = s + (double)p2;
+          st.c = c_new;
+        } else if (over > 1.f) {       // keep the dominant terms' exponents small: their rounding scales with |exponent|
+          const float c_new = m_new * kLog2e;
+          st.s = (st.s + (double)p) * (double)__builtin_amdgcn_exp2f(st.c - c_new);
+          st.c = c_new;
+        } else {
+          st.s += (double)p;
+        }
+        st.m = m_new;
+        __syncthreads();
+      }
+    } else {
+    // ---- epilogue of the other modes: four 64-column quarters through a row-major staging area;
+    // thread t owns row t and its 64 consecutive columns
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
       if (wn == (qd >> 1)) {
@@ -483,45 +577,10 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
             }
             b_others += (double)part;
           }
-        } else
-        if (ncols > 0) {
-          // One pass over the 64 new logits: maximum, sum of exp2 against the reference exponent the
-          // row already has (st.c, at most 2 below its maximum in the log2 domain), and the top-k
-          // insertions.  The sum is re-referenced when the maximum has moved more than that above st.c,
-          // and recomputed in the rare case that the old reference could have overflowed (or when the
-          // row has none yet).
-          const bool have_ref = (st.m != neg_inf());
-          const float c_ref = have_ref ? st.c : 0.f;
-          float cm = neg_inf(), p = 0.f;
-          for (int c2 = 0; c2 < ncols; ++c2) {
-            const float x = mine[c2];
-            cm = fmaxf(cm, x);
-            p += __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, -c_ref));
-            if (x >= st.v[KT - 1]) {
-              const int xi = cbase + c2;
-              if (better(x, xi, st.v[KT - 1], st.id[KT - 1])) list_insert<KT>(st.v, st.id, x, xi);
-            }
-          }
-          const float m_new = fmaxf(st.m, cm);
-          const float over = __builtin_fmaf(cm, kLog2e, -c_ref);     // how far the new maximum is above the reference
-          if (!have_ref || over > 100.f) {
-            const float c_new = (m_new == neg_inf()) ? 0.f : m_new * kLog2e;
-            float p2 = 0.f;
-            for (int c2 = 0; c2 < ncols; ++c2) p2 += __builtin_amdgcn_exp2f(__builtin_fmaf(mine[c2], kLog2e, -c_new));
-            const double s = have_ref ? st.s * (double)__builtin_amdgcn_exp2f(st.c - c_new) : 0.0;
-            st.s = s + (double)p2;
-            st.c = c_new;
-          } else if (over > 1.f) {       // keep the dominant terms' exponents small: their rounding scales with |exponent|
-            const float c_new = m_new * kLog2e;
-            st.s = (st.s + (double)p) * (double)__builtin_amdgcn_exp2f(st.c - c_new);
-            st.c = c_new;
-          } else {
-            st.s += (double)p;
-          }
-          st.m = m_new;
         }
       }
       __syncthreads();
+    }
     }
   }
 

@@ -26,10 +26,8 @@ constexpr int FROWB = FBK * 2;                     // bytes per staged row (bf16
 constexpr int FSTAGE_B = (FBM + FBN) * FROWB;      // bytes per stage: 256 hidden rows, then 256 W rows
 constexpr int FNST = 4;                            // LDS stages: one being multiplied, FNST-1 landing (3 and 5 measured slower)
 constexpr int FKT = 16;                            // capacity of the per-thread top list
-constexpr int FSTG_LD = 65;                        // staging row stride (floats), row-major staging
 constexpr int FSTG_CM = FBM + 4;                   // staging column stride (floats), column-major staging
 constexpr size_t kFusedLdsBytes = (size_t)FNST * FSTAGE_B;
-static_assert(kFusedLdsBytes >= (size_t)FBM * FSTG_LD * sizeof(float), "staging area must fit");
 static_assert(kFusedLdsBytes >= (size_t)64 * FSTG_CM * sizeof(float), "staging area must fit");
 static_assert(63 * FSTG_CM * sizeof(float) < 65536, "a row's 64 staged columns are reached with immediate offsets");
 static_assert(FNST == 4, "the wait counts and the issue order of the main loop are written for this ring");
@@ -291,13 +289,18 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
   // the list keeps the KT >= ktop best of the row; its last entry is the insertion threshold
   RowState<KT> st;
   const int ktop = a.ktop;
-  // backward mode: thread t writes coef * (-softmax) of row t and sums the probabilities of all
-  // tokens but the accepted one
-  float b_lse = 0.f, b_coef = 0.f;
-  int b_tok = -1;
-  float *b_out = nullptr;
-  double b_others = 0.0;
-  uint16_t *p_hi = nullptr, *p_lo = nullptr;
+  // Writing modes (backward, planes, store): a wave writes the rows 64 wave .. 64 wave + 63 of the tile, eight
+  // at a time; lane l then holds four consecutive columns (4 (l % 8) ..) of row 8 it + l / 8, so that the eight
+  // lanes of a row write 128 contiguous bytes of an fp32 row (64 of a bf16 plane) per store instruction.  A
+  // lane therefore keeps the parameters of its eight rows (it = 0..7) for the whole patch row.
+  constexpr bool kWrites = (MODE != kFusedStats);
+  constexpr int NR = kWrites ? 8 : 1;
+  float e_lse[NR], e_coef[NR];
+  int e_tok[NR];
+  int64_t e_base[NR];        // element offset of the row in the output (gradient rows / planes / stored rows); -1: no row
+  double e_others[NR];       // backward and planes: sum of the probabilities of all tokens but the accepted one
+#pragma unroll
+  for (int it = 0; it < NR; ++it) { e_lse[it] = 0.f; e_coef[it] = 0.f; e_tok[it] = -1; e_base[it] = -1; e_others[it] = 0.0; }
   const uint16_t *a_ptr[4] = {nullptr, nullptr, nullptr, nullptr};
   int64_t row0 = 0;
   int cur_P = -1;
@@ -305,21 +308,32 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
 
   // partial results of the row-block segment that ends (patch row finished, or the group's range did)
   auto flush = [&]() {
-    const int64_t g = row0 + tid;
-    if (MODE == kFusedStore || g >= M) return;
-    const int64_t pi = g * n_slots + slot;
-    if (MODE == kFusedBwd || MODE == kFusedPlanes) {
-      a.part_s[pi] = b_others;
+    if constexpr (MODE == kFusedStore) {
       return;
-    }
-    a.part_m[pi] = st.m;
-    a.part_c[pi] = st.c;
-    a.part_s[pi] = st.s;
+    } else if constexpr (kWrites) {
+      // the eight lanes of a row add up their column groups (fixed order), lane 0 of the eight writes
 #pragma unroll
-    for (int i = 0; i < KT; ++i) {
-      if (i < ktop) {
-        a.part_v[pi * ktop + i] = st.v[i];
-        a.part_i[pi * ktop + i] = st.id[i];
+      for (int it = 0; it < NR; ++it) {
+        double v = e_others[it];
+        v += __shfl_xor(v, 1, kWave);
+        v += __shfl_xor(v, 2, kWave);
+        v += __shfl_xor(v, 4, kWave);
+        const int64_t g = row0 + wave * 64 + 8 * it + (lane >> 3);
+        if ((lane & 7) == 0 && g < M) a.part_s[g * n_slots + slot] = v;
+      }
+    } else {
+      const int64_t g = row0 + tid;
+      if (g >= M) return;
+      const int64_t pi = g * n_slots + slot;
+      a.part_m[pi] = st.m;
+      a.part_c[pi] = st.c;
+      a.part_s[pi] = st.s;
+#pragma unroll
+      for (int i = 0; i < KT; ++i) {
+        if (i < ktop) {
+          a.part_v[pi * ktop + i] = st.v[i];
+          a.part_i[pi * ktop + i] = st.id[i];
+        }
       }
     }
   };
@@ -336,7 +350,8 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
       st.m = neg_inf(); st.c = 0.f; st.s = 0.0;
 #pragma unroll
       for (int i = 0; i < KT; ++i) { st.v[i] = neg_inf(); st.id[i] = kNoId; }
-      b_others = 0.0; b_out = nullptr; p_hi = nullptr; p_lo = nullptr; b_tok = -1;
+#pragma unroll
+      for (int it = 0; it < NR; ++it) { e_base[it] = -1; e_others[it] = 0.0; e_tok[it] = -1; }
       if (rows_live) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -345,19 +360,21 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
           const int64_t hs = a.row_list ? (int64_t)a.row_list[g] : used_slot_index(g, a.rho, a.d, a.kslots);
           a_ptr[j] = Hp + hs * HD + ld_unit * 8;
         }
-        if (MODE == kFusedBwd || MODE == kFusedPlanes) {
-          const int64_t gme = row0 + tid;
-          if (gme < M) {
-            const int pidx = a.list_p[gme];
-            const int rr = pidx / a.d;
-            b_lse = a.lse_by_slot[a.row_list[gme]];
-            b_coef = a.coef[rr];
-            b_tok = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
-            if (MODE == kFusedBwd) {
-              b_out = a.grad_rows + (int64_t)pidx * a.V;
-            } else {
-              p_hi = a.plane_hi + gme * a.V;
-              p_lo = a.plane_lo + gme * a.V;
+        if constexpr (kWrites) {
+#pragma unroll
+          for (int it = 0; it < NR; ++it) {
+            const int64_t gme = row0 + wave * 64 + 8 * it + (lane >> 3);
+            if (gme < M) {
+              if constexpr (MODE == kFusedStore) {
+                e_base[it] = gme * a.store_pitch;
+              } else {
+                const int pidx = a.list_p[gme];
+                const int rr = pidx / a.d;
+                e_lse[it] = a.lse_by_slot[a.row_list[gme]];
+                e_coef[it] = a.coef[rr];
+                e_tok[it] = a.sel_tok[(int64_t)rr * a.g + a.path_node[pidx]];
+                e_base[it] = (MODE == kFusedBwd) ? (int64_t)pidx * a.V : gme * (int64_t)a.V;
+              }
             }
           }
         }
@@ -483,104 +500,90 @@ __global__ __launch_bounds__(256) void k_fused_rows(FusedArgs a) {
         __syncthreads();
       }
     } else {
-    // ---- epilogue of the other modes: four 64-column quarters through a row-major staging area;
-    // thread t owns row t and its 64 consecutive columns
+      // ---- epilogue of the writing modes: the same four phases and the same column-major staging; then
+      // every wave walks its 64 rows eight at a time (see the lane mapping above), two pieces of 32 columns each
+      const bool vec4 = ((a.V & 3) == 0) && (MODE != kFusedStore || (a.store_pitch & 3) == 0);
 #pragma unroll
-    for (int qd = 0; qd < 4; ++qd) {
-      if (wn == (qd >> 1)) {
+      for (int nt = 0; nt < 4; ++nt) {
+        {
+          float *wcol = stg + (wn * 32 + (lane & 31)) * FSTG_CM + wm * 128 + 4 * (lane >> 5);
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+          for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-          for (int n2 = 0; n2 < 2; ++n2) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int row = wm * 128 + mt * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-              const int col = n2 * 32 + (lane & 31);
-              stg[row * FSTG_LD + col] = acc[mt][(qd & 1) * 2 + n2][e];
+            for (int g4 = 0; g4 < 4; ++g4) {
+              const f32x4 q = {acc[mt][nt][4 * g4], acc[mt][nt][4 * g4 + 1], acc[mt][nt][4 * g4 + 2],
+                               acc[mt][nt][4 * g4 + 3]};
+              *reinterpret_cast<f32x4 *>(wcol + mt * 32 + 8 * g4) = q;
             }
-            __builtin_amdgcn_sched_barrier(0);   // 16 accumulator reads at a time keep the register pressure low
+            __builtin_amdgcn_sched_barrier(0);
           }
-      }
-      __syncthreads();
-      {
-        const float *mine = stg + tid * FSTG_LD;
-        const int cbase = n0 + qd * 64;
-        const int ncols = min(64, a.V - cbase);     // <= 0 for quarters beyond the vocabulary
-        if (MODE == kFusedStore) {
-          const int64_t gme = row0 + tid;
-          if (ncols > 0 && gme < M) {
-            float *o = a.store_rows + gme * a.store_pitch + cbase;
-            if (ncols == 64) {
+        }
+        __syncthreads();
 #pragma unroll
-              for (int c4 = 0; c4 < 64; c4 += 4) {
-                const f32x4 q = {mine[c4], mine[c4 + 1], mine[c4 + 2], mine[c4 + 3]};
-                *reinterpret_cast<f32x4 *>(o + c4) = q;
-              }
-            } else {
-              for (int c2 = 0; c2 < ncols; ++c2) o[c2] = mine[c2];
-            }
-          }
-        } else
-        if (MODE == kFusedPlanes) {
-          // -coef * softmax as hi + lo in bf16 (V is a multiple of 32 in this mode: whole 16-byte stores);
-          // the accepted token's entry is left out (zero) and the other probabilities are summed, so that
-          // its coefficient coef * (1 - p_token) can be formed without cancellation afterwards
-          if (ncols > 0 && p_hi != nullptr) {
-            float part = 0.f;
-            for (int c8 = 0; c8 < ncols; c8 += 8) {
-              uint16_t hq[8], lq[8];
+        for (int it = 0; it < NR; ++it) {
+          const float *src = stg + wave * 64 + 8 * it + (lane >> 3);
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const bool is_tok = (cbase + c8 + e == b_tok);
-                const float pv = is_tok ? 0.f : __builtin_amdgcn_exp2f((mine[c8 + e] - b_lse) * kLog2e);
-                part += pv;
-                const float gv = -b_coef * pv;
-                const __bf16 hb = (__bf16)gv;
-                const __bf16 lb = (__bf16)(gv - (float)hb);
-                hq[e] = __builtin_bit_cast(uint16_t, hb);
-                lq[e] = __builtin_bit_cast(uint16_t, lb);
-              }
-              u32x4 ho, lo;
+          for (int piece = 0; piece < 2; ++piece) {
+            const int c0 = piece * 32 + 4 * (lane & 7);                       // staged column of this lane's first element
+            const int col = n0 + piece * 128 + nt * 32 + 4 * (lane & 7);      // its vocabulary entry
+            if (e_base[it] < 0 || col >= a.V) continue;
+            float x[4];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                ho[e] = (uint32_t)hq[2 * e] | ((uint32_t)hq[2 * e + 1] << 16);
-                lo[e] = (uint32_t)lq[2 * e] | ((uint32_t)lq[2 * e + 1] << 16);
-              }
-              *reinterpret_cast<u32x4 *>(p_hi + cbase + c8) = ho;
-              *reinterpret_cast<u32x4 *>(p_lo + cbase + c8) = lo;
-            }
-            b_others += (double)part;
-          }
-        } else
-        if (MODE == kFusedBwd) {
-          if (ncols > 0 && b_out != nullptr) {
-            float part = 0.f;
-            const bool vec = ((a.V & 3) == 0) && (ncols == 64);
-            for (int c4 = 0; c4 < ncols; c4 += 4) {
-              float gq[4];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int c2 = c4 + e;
-                const float x = (c2 < ncols) ? mine[c2] : neg_inf();
-                const float pv = __builtin_amdgcn_exp2f((x - b_lse) * kLog2e);
-                part += (cbase + c2 == b_tok) ? 0.f : pv;
-                gq[e] = -b_coef * pv;
-              }
-              if (vec) {
-                const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(b_out + cbase + c4));
+            for (int e = 0; e < 4; ++e) x[e] = src[(c0 + e) * FSTG_CM];
+            const bool whole = vec4 && (col + 3 < a.V);
+            if constexpr (MODE == kFusedStore) {
+              float *o = a.store_rows + e_base[it] + col;
+              if (whole) {
+                const f32x4 q = {x[0], x[1], x[2], x[3]};
+                *reinterpret_cast<f32x4 *>(o) = q;
               } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                  if (c4 + e < ncols) b_out[cbase + c4 + e] = gq[e];
+                  if (col + e < a.V) o[e] = x[e];
+              }
+            } else {
+              // -coef * softmax; the accepted token's probability is left out of the sum (and, in the planes, out
+              // of the entry) so that its coefficient coef * (1 - p_token) can be formed without cancellation
+              float gq[4], part = 0.f;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const bool is_tok = (col + e == e_tok[it]);
+                float pv = (col + e < a.V) ? __builtin_amdgcn_exp2f((x[e] - e_lse[it]) * kLog2e) : 0.f;
+                if (MODE == kFusedPlanes && is_tok) pv = 0.f;
+                part += is_tok ? 0.f : pv;
+                gq[e] = -e_coef[it] * pv;
+              }
+              e_others[it] += (double)part;
+              if constexpr (MODE == kFusedBwd) {
+                float *o = a.grad_rows + e_base[it] + col;
+                if (whole) {
+                  const f32x4 q = {gq[0], gq[1], gq[2], gq[3]};
+                  __builtin_nontemporal_store(q, reinterpret_cast<f32x4 *>(o));
+                } else {
+#pragma unroll
+                  for (int e = 0; e < 4; ++e)
+                    if (col + e < a.V) o[e] = gq[e];
+                }
+              } else {
+                // planes: value = hi + lo in bf16 (V is a multiple of 32 in this mode: whole 8-byte stores)
+                uint16_t hq[4], lq[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const __bf16 hb = (__bf16)gq[e];
+                  const __bf16 lb = (__bf16)(gq[e] - (float)hb);
+                  hq[e] = __builtin_bit_cast(uint16_t, hb);
+                  lq[e] = __builtin_bit_cast(uint16_t, lb);
+                }
+                const u32x2 ho = {(uint32_t)hq[0] | ((uint32_t)hq[1] << 16), (uint32_t)hq[2] | ((uint32_t)hq[3] << 16)};
+                const u32x2 lo = {(uint32_t)lq[0] | ((uint32_t)lq[1] << 16), (uint32_t)lq[2] | ((uint32_t)lq[3] << 16)};
+                *reinterpret_cast<u32x2 *>(a.plane_hi + e_base[it] + col) = ho;
+                *reinterpret_cast<u32x2 *>(a.plane_lo + e_base[it] + col) = lo;
               }
             }
-            b_others += (double)part;
           }
         }
+        __syncthreads();
       }
-      __syncthreads();
-    }
     }
   }
 

@@ -5,11 +5,15 @@
 //  k_fused_rows  : 256 x 256 output tile per workgroup iteration (4 waves, each 128 x 128 as 4 x 4
 //                  MFMA 32x32x16 bf16 tiles, fp32 accumulators).  K slabs of 32 go from global
 //                  memory straight into a ring of four LDS stages (no register staging), three
-//                  slabs in flight while one is multiplied.
-//                  A workgroup owns 256 rows and sweeps a chunk of the vocabulary; after each
-//                  tile the accumulators are staged through LDS so that thread t owns row t and
-//                  folds its 256 new logits into its running (max, sum, top-k list) in registers.
-//  k_fused_merge : combines the per-chunk partials of a row into the final statistics.
+//                  slabs in flight while one is multiplied.  The launch is persistent (one
+//                  workgroup per compute unit); a workgroup keeps its 256 rows while it moves
+//                  along a patch row of the tile grid.  After each tile the accumulators are staged
+//                  through LDS column-major; in the statistics passes thread t owns row t and folds
+//                  its 256 new logits into its running (max, sum, top-k list) in registers; in the
+//                  writing passes (gradient rows, bf16 planes, stored logits) the eight lanes of a
+//                  row write contiguous bytes.
+//  k_fused_merge : combines the partial results of a row (one per group and column phase) into the
+//                  final statistics.
 //  k_gather_dot  : single logits (hidden row . W row) for the few (row, token) pairs the reward
 //                  and the surrogate need.
 #include "gto_device.h"

@@ -392,7 +392,7 @@ def main():
     ap.add_argument("--roots", type=int, default=0, help="override the number of roots (debug)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per row in the row kernels (tuning)")
     ap.add_argument("--fused-groups", type=int, default=0, help="fused variant: vocabulary chunks per row block (tuning)")
-    ap.add_argument("--fused-layout", type=int, default=0, help="fused variant: 0 per-XCD patches, 1 row-major (tuning)")
+    ap.add_argument("--fused-layout", type=int, default=0, help="fused variant: workgroups of a group as 0 = 8 row blocks x 4 column tiles, 1 = 4 x 8 (tuning)")
     ap.add_argument("--no-prune", action="store_true",
                     help="stream every used target row instead of only those the kept tree refers to")
     ap.add_argument("--no-extras", action="store_true", help="skip the token-level loss and the hidden-state backward")

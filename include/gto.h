@@ -91,10 +91,10 @@ typedef struct gto_config {
   int32_t waves_per_row;  /* wavefronts sharing one logits row in the row kernels: 0 (chosen per
                              launch from V and the number of rows), 1, 2, 4 or 8; else GTO_E_MODE */
   int32_t fused_groups;   /* fused variant: groups of workgroups the row pass is launched with, 0 (= 8: one
-                             group per XCD, one workgroup per compute unit) .. 8 (16 with fused_layout 1);
+                             group per XCD, one workgroup per compute unit) .. 16 (8 with fused_layout 1);
                              else GTO_E_MODE.  Sizes the fused workspace.                          */
-  int32_t fused_layout;   /* fused variant: a group is 0 = 4 row blocks x 8 column tiles of workgroups
-                             (default), 1 = 8 x 4                                                  */
+  int32_t fused_layout;   /* fused variant: a group is 0 = 8 row blocks x 4 column tiles of workgroups
+                             (the library's choice), 1 = 4 x 8                                     */
   int32_t reserved;       /* must be 0                                                          */
 } gto_config;
 

@@ -146,7 +146,7 @@ int check_cfg(const gto_config *c, bool need_group) {
   const int wpr = c->waves_per_row;
   if (!(wpr == 0 || wpr == 1 || wpr == 2 || wpr == 4 || wpr == 8)) return GTO_E_MODE;
   if (c->fused_layout != 0 && c->fused_layout != 1) return GTO_E_MODE;
-  if (c->fused_groups < 0 || c->fused_groups > (c->fused_layout == 0 ? 8 : 16) || c->reserved != 0) return GTO_E_MODE;
+  if (c->fused_groups < 0 || c->fused_groups > (c->fused_layout == 0 ? 16 : 8) || c->reserved != 0) return GTO_E_MODE;
   if (c->path_mode != GTO_PATH_GREEDY && c->path_mode != GTO_PATH_MAX_L && c->path_mode != GTO_PATH_SAMPLED)
     return GTO_E_MODE;
   if (need_group && (c->group_size < 1 || c->R % c->group_size != 0)) return GTO_E_SHAPE;
@@ -331,14 +331,15 @@ int check_fused(const gto_config *c, const void *hidden, int hidden_dim, const v
 
 // Launch geometry of the row pass (see the work distribution in gto_fused.hip): `groups` groups of
 // patch_rows x patch_cols workgroups, each row with groups * patch_cols partial results.  By default 8 groups
-// of 4 x 8: one group per XCD, one workgroup per compute unit.
+// of 8 x 4: one group per XCD, one workgroup per compute unit (8 x 4 and 4 x 8 take the same time; 8 x 4 streams
+// the head half as often, fetches a quarter less from the fabric and leaves half as many partial results).
 FusedPlan fused_plan(const gto_config *c, int64_t M, int ktop) {
   FusedPlan p{};
   p.M = M;
   p.n_tiles = (c->V + 255) / 256;
   p.groups = c->fused_groups > 0 ? c->fused_groups : 8;
-  p.patch_rows = c->fused_layout == 0 ? 4 : 8;
-  p.patch_cols = c->fused_layout == 0 ? 8 : 4;
+  p.patch_rows = c->fused_layout == 0 ? 8 : 4;
+  p.patch_cols = c->fused_layout == 0 ? 4 : 8;
   p.n_slots = p.groups * p.patch_cols;
   const size_t rows = (size_t)M * p.n_slots;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };

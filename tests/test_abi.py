@@ -102,7 +102,8 @@ def test_validation_errors_without_gpu():
     assert G.gto_workspace_bytes(_cfg()) == 256
     # tuning fields travel in the config and are validated like everything else
     assert _status(G.gto_draft_row_stats, _cfg(waves_per_row=3), fake, fd) == E["mode"]
-    assert _status(G.gto_draft_row_stats, _cfg(fused_groups=9), fake, fd) == E["mode"]
+    assert _status(G.gto_draft_row_stats, _cfg(fused_groups=17), fake, fd) == E["mode"]
+    assert _status(G.gto_draft_row_stats, _cfg(fused_groups=9, fused_layout=1), fake, fd) == E["mode"]
     assert _status(G.gto_draft_row_stats, _cfg(fused_layout=2), fake, fd) == E["mode"]
     # NaN / inf / negative parameters are rejected by bit tests (the library is built with NaNs not honoured)
     for bad in (float("nan"), float("inf"), -1.0):

@@ -257,7 +257,7 @@ def test_fused_chunking_and_layout_do_not_change_results(gpu_device):
                         w_corr=0.9, ref_sigma=0.05)
     t = S.make_fused(w, gpu_device)
     ref = _run(w, t, gpu_device)
-    for nc, layout in ((1, 1), (3, 0), (8, 1), (16, 1)):
+    for nc, layout in ((1, 1), (3, 0), (8, 1), (16, 0)):
         other = _run(w, t, gpu_device, fused_groups=nc, fused_layout=layout)
         for tag in ("cur", "ref"):
             for grp in ("tree", "reward"):

@@ -61,7 +61,7 @@ def test_random_shapes_streaming(gpu_device, seed):
 
 def test_random_shapes_fused(gpu_device):
     rng = random.Random(1)
-    for it in range(10):
+    for it in range(14):
         k = rng.choice([1, 2, 4, 5, 8, 10, 16])
         d = rng.choice([1, 2, 3, 4])
         C = k + (d - 1) * k * k
@@ -69,7 +69,8 @@ def test_random_shapes_fused(gpu_device):
         m = rng.choice([1, 2, 8])
         R = m * rng.choice([1, 2, 5])
         hidden = rng.choice([64, 128, 192, 256, 448])
-        V = max(((k + 7) // 8) * 8, rng.choice([8, 64, 200, 256, 1032, 2048, 3000, 4104]))
+        # rows are 16-byte aligned (V % 8 == 0 for bf16); sizes around the 32/64/128/256-column units of the epilogue
+        V = max(((k + 7) // 8) * 8, rng.choice([8, 64, 72, 200, 256, 1000, 1032, 2048, 2056, 3000, 4104]))
         corr = rng.choice([0.0, 0.8, 0.95])
         w = S.FusedWorkload(f"rnd{it}", R=R, V=V, k=k, d=d, g=g, m=m, hidden=hidden, h_scale=3.0, w_sigma=0.05,
                             w_corr=corr, ref_sigma=0.05, seed=5000 + it)

@@ -291,6 +291,29 @@ __device__ __forceinline__ void load4<float>(const float *row, int q4, float *x)
   const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + q4);
   x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
 }
+// The same four elements as they come from memory (to be carried across loop trips without the unpacking
+// being scheduled right behind the load), and their conversion.
+template <typename T> struct Raw4;
+template <> struct Raw4<uint16_t> {
+  typedef u32x2 type;
+  __device__ static __forceinline__ type load(const uint16_t *row, int q4) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(row) + q4);
+  }
+  __device__ static __forceinline__ void unpack(const type &q, float *x) {
+    x[0] = __uint_as_float(q.x << 16); x[1] = __uint_as_float(q.x & 0xffff0000u);
+    x[2] = __uint_as_float(q.y << 16); x[3] = __uint_as_float(q.y & 0xffff0000u);
+  }
+};
+template <> struct Raw4<float> {
+  typedef u32x4 type;
+  __device__ static __forceinline__ type load(const float *row, int q4) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row) + q4);
+  }
+  __device__ static __forceinline__ void unpack(const type &q, float *x) {
+    x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y); x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+  }
+};
+
 // N consecutive elements at element index N * idx: N == 4 as above; N == the elements of a 16-byte
 // vector for kernels that only read (16-byte loads stream ~20 % faster than 8-byte ones, measured).
 template <typename T, int N>
@@ -337,24 +360,31 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
   float others = 0.f;
   bool own_tok = false;
   if (VEC) {
-    // groups of four elements, kBwdUnroll groups in flight per lane: only a few hundred rows carry a
-    // gradient, so the bytes in flight have to come from inside a row
+    // Groups of four elements, kBwdUnroll groups per step and lane.  The loads of the next step are issued
+    // before the stores of this one: loads and stores share one in-order counter, so a wait for loads that
+    // were issued after a batch of stores would also wait for those stores to be acknowledged by memory.
     constexpr int kBwdUnroll = 4;
     const int n4 = V / 4;
-    for (int i0 = threadIdx.x; i0 < n4; i0 += kBwdUnroll * kBwdThreads) {
-      float x[kBwdUnroll][4];
+    typedef typename Raw4<T>::type raw_t;
+    raw_t x[kBwdUnroll], xn[kBwdUnroll];
+    // (past the end of the row the last group is fetched again: a branch around a load would end in a wait
+    // for everything outstanding)
+    auto fetch = [&](raw_t (&dst)[kBwdUnroll], int i0) {
 #pragma unroll
-      for (int u = 0; u < kBwdUnroll; ++u)
-        if (i0 + u * kBwdThreads < n4) load4<T>(row, i0 + u * kBwdThreads, x[u]);
+      for (int u = 0; u < kBwdUnroll; ++u) dst[u] = Raw4<T>::load(row, min(i0 + u * kBwdThreads, n4 - 1));
+    };
+    auto emit = [&](const raw_t (&src)[kBwdUnroll], int i0) {
 #pragma unroll
       for (int u = 0; u < kBwdUnroll; ++u) {
         const int i = i0 + u * kBwdThreads;
         if (i >= n4) continue;
+        float xv[4];
+        Raw4<T>::unpack(src[u], xv);
         float gq[4];
         float part = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p = __builtin_amdgcn_exp2f((x[u][e] - lse) * kLog2e);
+          const float p = __builtin_amdgcn_exp2f((xv[e] - lse) * kLog2e);
           gq[e] = -coef * p;
           const bool is_tok = (i * 4 + e == tok);
           own_tok = own_tok || is_tok;
@@ -364,6 +394,15 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
         const f32x4 o = {gq[0], gq[1], gq[2], gq[3]};
         __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(out) + i);
       }
+    };
+    // two steps per trip, the two register sets swapping roles (no copies between them)
+    constexpr int kStep = kBwdUnroll * kBwdThreads;
+    fetch(x, threadIdx.x);
+    for (int i0 = threadIdx.x; i0 < n4; i0 += 2 * kStep) {
+      fetch(xn, i0 + kStep);
+      emit(x, i0);
+      fetch(x, i0 + 2 * kStep);
+      emit(xn, i0 + kStep);
     }
   } else {
     for (int i = threadIdx.x; i < V; i += blockDim.x) {
@@ -412,12 +451,14 @@ __global__ __launch_bounds__(kTokThreads) void k_token_loss(TokenLossArgs a) {
   const int n4 = VEC ? V / kGroup : 0;
   for (int i0 = threadIdx.x; i0 < n4; i0 += kUnroll * kTokThreads) {
     float xd[kUnroll][kGroup], xt[kUnroll][kGroup];
+    // past the end of the rows the last group is fetched again (a branch around a load would end in a wait
+    // for everything outstanding)
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-      if (i0 + u * kTokThreads < n4) {
-        load_group<T, kGroup>(drow, i0 + u * kTokThreads, xd[u]);
-        load_group<T, kGroup>(trow, i0 + u * kTokThreads, xt[u]);
-      }
+    for (int u = 0; u < kUnroll; ++u) {
+      const int i = min(i0 + u * kTokThreads, n4 - 1);
+      load_group<T, kGroup>(drow, i, xd[u]);
+      load_group<T, kGroup>(trow, i, xt[u]);
+    }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int i = i0 + u * kTokThreads;

@@ -332,8 +332,11 @@ __device__ __forceinline__ void load_group(const T *row, int idx, float *x) {
 constexpr int kBwdThreads = 1024;
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
-  const int r = blockIdx.x / a.d;
-  const int t = blockIdx.x - r * a.d;
+  // step-major order: the rows that carry a gradient (short paths: mostly the first steps) then sit densely at
+  // the front of the grid and spread over the compute units (root-major order: 106 us instead of 80)
+  const int n_roots = gridDim.x / a.d;
+  const int t = blockIdx.x / n_roots;
+  const int r = blockIdx.x - t * n_roots;
   const int64_t rt = (int64_t)r * a.d + t;
   const int j = a.path_slot[rt];
   const float coef = a.coef[r];
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(kBwdThreads) void k_ppo_bwd(PpoBwdArgs a) {
     // Groups of four elements, kBwdUnroll groups per step and lane.  The loads of the next step are issued
     // before the stores of this one: loads and stores share one in-order counter, so a wait for loads that
     // were issued after a batch of stores would also wait for those stores to be acknowledged by memory.
-    constexpr int kBwdUnroll = 4;
+    constexpr int kBwdUnroll = 8;
     const int n4 = V / 4;
     typedef typename Raw4<T>::type raw_t;
     raw_t x[kBwdUnroll], xn[kBwdUnroll];

@@ -12,7 +12,8 @@ LLaMA-3.1-8B-shaped, V = 128256): trees scored per second (value), `roofline` fo
 kernel (the draft row kernel; algorithmic bytes / HIP-event time measured on the launch stream
 inside the timed region) and `cpu_baseline` (the CPU oracle, fanned out over the machine's host
 cores, timed on a bounded sample of the same workload).  `all_configs` carries one entry per
-configuration (five, plus the fused configuration's companion with a correlated target head):
+configuration (five, plus the headline workload with one group over the whole batch and the fused
+configuration's companion with a correlated target head):
 ms/step, trees/s, the dominant kernel's fraction of its roofline, the rows streamed, the
 per-kernel durations with their algorithmic bytes or flops, and the oracle's near-tie count on
 the sampled roots.
@@ -447,6 +448,15 @@ def main():
                         continue
                     log(f"all_configs: {name}")
                     entries.append(summary(run(name, steps, warmup, cpu_roots if args.cpu_roots > 0 else 0)))
+                # the headline workload once more with the advantage standardised over the whole batch
+                # (one group of R roots) instead of groups of m
+                if not args.group_size:
+                    log(f"all_configs: {HEADLINE}, one group over the batch")
+                    args.group_size = S.CONFIGS[HEADLINE].R
+                    e = summary(run(HEADLINE, 5, 2, 0))
+                    args.group_size = 0
+                    e["workload"] += " [advantage standardised over the batch: one group of R roots]"
+                    entries.insert(3, e)
                 out["all_configs"] = entries
     finally:
         if P is not None:

@@ -11,7 +11,6 @@
 namespace gto {
 
 constexpr int kTreeThreads = 256;
-constexpr int kMaxLevelCands = 4096;  // k^2 for k <= 64
 constexpr int kMaxPool = 4096;        // C
 
 __device__ __forceinline__ uint64_t rank_key(float score, int index) {
@@ -19,24 +18,44 @@ __device__ __forceinline__ uint64_t rank_key(float score, int index) {
 }
 
 // ------------------------------------------------------------------------------ expansion
+// Which rows feed which candidate is fixed by the shape (candidate c of the pool is child rk of slot j of
+// level l), so every log-probability and token of the root is fetched up front in one round of loads; the
+// level loop then runs out of LDS and only stores to memory.
+// Dynamic LDS: k^2 keys rounded up to a multiple of eight (8 B each), C log-probabilities (4 B).
 __global__ __launch_bounds__(kTreeThreads) void k_expand(ExpandArgs a) {
   const int r = blockIdx.x;
-  const int k = a.k, d = a.d, kk = a.k * a.k;
+  const int k = a.k, d = a.d, kk = a.k * a.k, C = a.C;
   const int tid = threadIdx.x;
-  __shared__ uint64_t s_key[kMaxLevelCands];
+  extern __shared__ __align__(16) unsigned char s_dyn[];
+  const int kk8 = (kk + 7) & ~7;
+  uint64_t *s_key = reinterpret_cast<uint64_t *>(s_dyn);
+  float *s_lp = reinterpret_cast<float *>(s_key + kk8);
   __shared__ float s_score[2][64];
   __shared__ int s_cand[2][64];
-  const int64_t pool0 = (int64_t)r * a.C;
+  const int64_t pool0 = (int64_t)r * C;
   const int64_t slot0 = (int64_t)r * d * k;
 
+  for (int t = kk + tid; t < kk8; t += kTreeThreads) s_key[t] = 0ull;
+  for (int c = tid; c < C; c += kTreeThreads) {
+    int l = 0, j = 0, rk = c;
+    if (c >= k) {
+      const int q = c - k;
+      l = 1 + q / kk;
+      const int t = q - (l - 1) * kk;
+      j = t / k;
+      rk = t - j * k;
+    }
+    const int64_t si = stat_index(r, l, j, d, k) * k + rk;
+    s_lp[c] = a.top_logp[si];
+    a.cand_tok[pool0 + c] = a.top_tok[si];
+    a.cand_depth[pool0 + c] = l + 1;
+    a.cand_pslot[pool0 + c] = j;
+  }
+  __syncthreads();
   // level 0: the root's k children, all expanded at level 1 in rank order
   for (int t = tid; t < k; t += kTreeThreads) {
-    const int64_t si = stat_index(r, 0, 0, d, k) * k + t;
-    const float sc = __fadd_rn(0.f, a.top_logp[si]);
-    a.cand_tok[pool0 + t] = a.top_tok[si];
+    const float sc = __fadd_rn(0.f, s_lp[t]);
     a.cand_parent[pool0 + t] = -1;
-    a.cand_depth[pool0 + t] = 1;
-    a.cand_pslot[pool0 + t] = 0;
     a.cand_score[pool0 + t] = sc;
     a.cand_slot[pool0 + t] = (d > 1) ? t : -1;
     a.slot_cand[slot0 + t] = -1;
@@ -49,14 +68,10 @@ __global__ __launch_bounds__(kTreeThreads) void k_expand(ExpandArgs a) {
     const int cur = l & 1, nxt = cur ^ 1;
     const int base = k + (l - 1) * kk;
     for (int t = tid; t < kk; t += kTreeThreads) {
-      const int j = t / k, rk = t - j * k;
-      const int64_t si = stat_index(r, l, j, d, k) * k + rk;
-      const float sc = __fadd_rn(s_score[cur][j], a.top_logp[si]);
+      const int j = t / k;
+      const float sc = __fadd_rn(s_score[cur][j], s_lp[base + t]);
       const int c = base + t;
-      a.cand_tok[pool0 + c] = a.top_tok[si];
       a.cand_parent[pool0 + c] = s_cand[cur][j];
-      a.cand_depth[pool0 + c] = l + 1;
-      a.cand_pslot[pool0 + c] = j;
       a.cand_score[pool0 + c] = sc;
       s_key[t] = rank_key(sc, t);
       if (l == d - 1) a.cand_slot[pool0 + c] = -1;
@@ -66,10 +81,19 @@ __global__ __launch_bounds__(kTreeThreads) void k_expand(ExpandArgs a) {
     for (int t = tid; t < kk; t += kTreeThreads) {
       const uint64_t mine = s_key[t];
       int rank = 0;
-      for (int u = 0; u < kk; ++u) rank += (s_key[u] > mine) ? 1 : 0;
+      // eight keys per trip (the list is padded with zeros, which beat nothing): the reads of a trip are
+      // independent, one key per trip would pay the LDS latency kk times
+      for (int u = 0; u < kk8; u += 8) {
+        uint64_t q[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[e] = s_key[u + e];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) rank += (q[e] > mine) ? 1 : 0;
+      }
       const int c = base + t;
       if (rank < k) {
-        s_score[nxt][rank] = a.cand_score[pool0 + c];
+        // the same add as above gives the same bits; s_score[nxt] was last read before the previous barrier
+        s_score[nxt][rank] = __fadd_rn(s_score[cur][t / k], s_lp[base + t]);
         s_cand[nxt][rank] = c;
         a.slot_cand[slot0 + (int64_t)(l + 1) * k + rank] = c;
         a.cand_slot[pool0 + c] = rank;
@@ -82,30 +106,55 @@ __global__ __launch_bounds__(kTreeThreads) void k_expand(ExpandArgs a) {
 }
 
 void launch_expand(const ExpandArgs &a, hipStream_t st) {
-  hipLaunchKernelGGL(k_expand, dim3(a.R), dim3(kTreeThreads), 0, st, a);
+  const size_t lds = (size_t)((a.k * a.k + 7) & ~7) * 8 + (size_t)a.C * 4;
+  hipLaunchKernelGGL(k_expand, dim3(a.R), dim3(kTreeThreads), lds, st, a);
 }
 
 // ------------------------------------------------------------------------------ top-g
+// The C candidates of a root are sorted by their (unique) keys with a bitonic network over the next power of
+// two, padded with key 0 (below every real key: the low word of a real key is never 0).  Position i of the
+// sorted list is rank i; comparing every key with every other one, as the expansion does for its k^2 keys,
+// costs C^2 = 260 k compares per root at C = 510 and made this kernel ALU bound.
+// Dynamic LDS: n_pad keys (8 B), C ranks (4 B), n_keep leaf flags, d * k need flags.
+__device__ __forceinline__ int select_pad(int C) {
+  int n = 2;
+  while (n < C) n <<= 1;
+  return n;
+}
+
 __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
   const int r = blockIdx.x, tid = threadIdx.x;
   const int C = a.C, g = a.g;
   const int n_keep = (g < C) ? g : C;
-  __shared__ uint64_t s_key[kMaxPool];
-  __shared__ int s_rank[kMaxPool];
-  __shared__ unsigned char s_leaf[kMaxPool];
-  __shared__ unsigned char s_need[32 * 64];   // d * k flags
+  const int n_pad = select_pad(C);
+  extern __shared__ __align__(16) unsigned char s_dyn[];
+  uint64_t *s_key = reinterpret_cast<uint64_t *>(s_dyn);
+  int *s_rank = reinterpret_cast<int *>(s_key + n_pad);
+  unsigned char *s_leaf = reinterpret_cast<unsigned char *>(s_rank + C);
+  unsigned char *s_need = s_leaf + n_keep;
   const int64_t pool0 = (int64_t)r * C;
   const int64_t sel0 = (int64_t)r * g;
-  for (int c = tid; c < C; c += kTreeThreads) s_key[c] = rank_key(a.cand_score[pool0 + c], c);
+  for (int c = tid; c < n_pad; c += kTreeThreads) s_key[c] = (c < C) ? rank_key(a.cand_score[pool0 + c], c) : 0ull;
   for (int i = tid; i < n_keep; i += kTreeThreads) s_leaf[i] = 1;
   for (int i = tid; i < a.d * a.k; i += kTreeThreads) s_need[i] = 0;
   __syncthreads();
-  for (int c = tid; c < C; c += kTreeThreads) {
-    const uint64_t mine = s_key[c];
-    int rank = 0;
-    for (int u = 0; u < C; ++u) rank += (s_key[u] > mine) ? 1 : 0;
-    s_rank[c] = rank;
+  // descending bitonic sort
+  for (int size = 2; size <= n_pad; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < (n_pad >> 1); t += kTreeThreads) {
+        const int lo = 2 * t - (t & (stride - 1));
+        const int hi = lo + stride;
+        const bool desc = (lo & size) == 0;
+        const uint64_t x = s_key[lo], y = s_key[hi];
+        if ((x < y) == desc) {
+          s_key[lo] = y;
+          s_key[hi] = x;
+        }
+      }
+      __syncthreads();
+    }
   }
+  for (int i = tid; i < C; i += kTreeThreads) s_rank[(int)(0xffffffffu - (uint32_t)s_key[i])] = i;
   __syncthreads();
   for (int c = tid; c < C; c += kTreeThreads) {
     const int p = a.cand_parent[pool0 + c];
@@ -117,21 +166,20 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
     if (s_rank[c] < n_keep) s_need[(a.cand_depth[pool0 + c] - 1) * a.k + a.cand_pslot[pool0 + c]] = 1;
   }
   __syncthreads();
-  for (int c = tid; c < C; c += kTreeThreads) {
-    const int i = s_rank[c];
-    if (i < n_keep) {
-      const int p = a.cand_parent[pool0 + c];
-      a.sel_cand[sel0 + i] = c;
-      a.sel_tok[sel0 + i] = a.cand_tok[pool0 + c];
-      // a parent always outranks its child (log-probabilities are <= 0); the range check only matters for
-      // rows that held NaNs, whose values are unspecified but whose indices must stay inside the list
-      a.sel_parent[sel0 + i] = (p >= 0 && s_rank[p] < i) ? s_rank[p] : -1;
-      a.sel_depth[sel0 + i] = a.cand_depth[pool0 + c];
-      a.sel_pslot[sel0 + i] = a.cand_pslot[pool0 + c];
-      a.sel_slot[sel0 + i] = a.cand_slot[pool0 + c];
-      a.sel_score[sel0 + i] = a.cand_score[pool0 + c];
-      a.sel_leaf[sel0 + i] = s_leaf[i];
-    }
+  // the kept candidates, straight from the sorted list
+  for (int i = tid; i < n_keep; i += kTreeThreads) {
+    const int c = (int)(0xffffffffu - (uint32_t)s_key[i]);
+    const int p = a.cand_parent[pool0 + c];
+    a.sel_cand[sel0 + i] = c;
+    a.sel_tok[sel0 + i] = a.cand_tok[pool0 + c];
+    // a parent always outranks its child (log-probabilities are <= 0); the range check only matters for
+    // rows that held NaNs, whose values are unspecified but whose indices must stay inside the list
+    a.sel_parent[sel0 + i] = (p >= 0 && s_rank[p] < i) ? s_rank[p] : -1;
+    a.sel_depth[sel0 + i] = a.cand_depth[pool0 + c];
+    a.sel_pslot[sel0 + i] = a.cand_pslot[pool0 + c];
+    a.sel_slot[sel0 + i] = a.cand_slot[pool0 + c];
+    a.sel_score[sel0 + i] = a.cand_score[pool0 + c];
+    a.sel_leaf[sel0 + i] = s_leaf[i];
   }
   for (int i = n_keep + tid; i < g; i += kTreeThreads) {
     a.sel_cand[sel0 + i] = -1;
@@ -148,7 +196,11 @@ __global__ __launch_bounds__(kTreeThreads) void k_select(SelectArgs a) {
 }
 
 void launch_select(const SelectArgs &a, hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(a.R), dim3(kTreeThreads), 0, st, a);
+  int n_pad = 2;
+  while (n_pad < a.C) n_pad <<= 1;
+  const int n_keep = (a.g < a.C) ? a.g : a.C;
+  const size_t lds = (size_t)n_pad * 8 + (size_t)a.C * 4 + (size_t)n_keep + (size_t)a.d * a.k;
+  hipLaunchKernelGGL(k_select, dim3(a.R), dim3(kTreeThreads), lds, st, a);
 }
 
 // ------------------------------------------------------------------------------ reward
@@ -171,14 +223,21 @@ __device__ __forceinline__ double block_reduce(double v, double *scratch, bool i
   return out;
 }
 
+// most nodes a root can keep: min(g, C)
+__host__ __device__ inline int reward_nodes(const RewardArgs &a) {
+  const int C = a.k + (a.d - 1) * a.k * a.k;
+  return a.g < C ? a.g : C;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
   const int r = blockIdx.x, tid = threadIdx.x;
   const int d = a.d, k = a.k, g = a.g;
   const int n = a.n_sel[r];
   const int64_t sel0 = (int64_t)r * g;
-  __shared__ double s_logt[kMaxPool];
-  __shared__ int s_parent[kMaxPool];
+  extern __shared__ __align__(16) unsigned char s_dyn[];     // min(g, C) doubles, then as many ints
+  double *s_logt = reinterpret_cast<double *>(s_dyn);
+  int *s_parent = reinterpret_cast<int *>(s_logt + reward_nodes(a));
   __shared__ double s_red[kRewardThreads];
   __shared__ int s_found;
   const T *logits = static_cast<const T *>(a.target_logits);
@@ -342,8 +401,9 @@ __global__ __launch_bounds__(kRewardThreads) void k_reward(RewardArgs a) {
 }
 
 void launch_reward(const RewardArgs &a, hipStream_t st) {
-  if (a.dtype == 0) hipLaunchKernelGGL(k_reward<uint16_t>, dim3(a.R), dim3(kRewardThreads), 0, st, a);
-  else hipLaunchKernelGGL(k_reward<float>, dim3(a.R), dim3(kRewardThreads), 0, st, a);
+  const size_t lds = (size_t)reward_nodes(a) * 12;
+  if (a.dtype == 0) hipLaunchKernelGGL(k_reward<uint16_t>, dim3(a.R), dim3(kRewardThreads), lds, st, a);
+  else hipLaunchKernelGGL(k_reward<float>, dim3(a.R), dim3(kRewardThreads), lds, st, a);
 }
 
 // ------------------------------------------------------------------------------ advantage

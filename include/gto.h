@@ -371,6 +371,11 @@ int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_str
  * gto_profile_enable(0) stops recording; the pool lives until the thread ends. */
 int gto_profile_enable(int on);
 int gto_profile_read(const char **names, int32_t *launches, double *total_ms, int cap);
+/* Restricts the timing to the kernel of one name (the names gto_profile_read reports, e.g.
+ * "row_stats_draft"); NULL = every kernel again.  Two event records per launch leave a few
+ * microseconds between consecutive kernels, which a timed region that only needs one kernel's
+ * duration can do without.  Per calling thread, like the rest of the profiling state. */
+int gto_profile_filter(const char *kernel_name_or_null);
 
 #ifdef __cplusplus
 }

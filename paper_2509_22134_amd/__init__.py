@@ -16,5 +16,5 @@ from .binding import (  # noqa: F401
     gto_expand_tree_fused, gto_tree_reward_fused, gto_ppo_surrogate_fwd_fused, gto_ppo_surrogate_bwd_fused,
     gto_fused_dh_workspace_bytes, gto_ppo_surrogate_bwd_fused_dh, gto_fused_token_loss_workspace_bytes,
     gto_token_loss_fwd_fused, gto_token_loss_bwd_fused,
-    gto_profile_enable, gto_profile_read,
+    gto_profile_enable, gto_profile_read, gto_profile_filter,
 )

@@ -117,11 +117,12 @@ def lib():
                                                  P(gto_draft_stats), VP, VP, VP, SZ, VP]
     L.gto_profile_enable.argtypes = [C.c_int]
     L.gto_profile_read.argtypes = [P(C.c_char_p), P(C.c_int32), P(C.c_double), C.c_int]
+    L.gto_profile_filter.argtypes = [C.c_char_p]
     for name in ("gto_workspace_bytes", "gto_draft_row_stats", "gto_target_row_stats", "gto_expand_tree",
                  "gto_expand_from_stats", "gto_select_topg", "gto_tree_reward", "gto_reward_from_stats",
                  "gto_group_advantage", "gto_ppo_surrogate_fwd", "gto_ppo_surrogate_bwd",
                  "gto_ppo_surrogate_fwd_noalloc",
-                 "gto_profile_enable", "gto_profile_read", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
+                 "gto_profile_enable", "gto_profile_read", "gto_profile_filter", "gto_calibration_copy", "gto_token_loss_fwd", "gto_token_loss_bwd",
                  "gto_fused_workspace_bytes", "gto_fused_draft_row_stats", "gto_fused_target_row_stats",
                  "gto_expand_tree_fused", "gto_tree_reward_fused",
                  "gto_ppo_surrogate_fwd_fused", "gto_ppo_surrogate_bwd_fused",
@@ -455,6 +456,10 @@ def gto_calibration_copy(src, dst, stream=None):
 
 def gto_profile_enable(on: bool) -> None:
     _check(lib().gto_profile_enable(1 if on else 0), "gto_profile_enable")
+
+
+def gto_profile_filter(kernel_name=None) -> None:
+    _check(lib().gto_profile_filter(kernel_name.encode() if kernel_name else None), "gto_profile_filter")
 
 
 def gto_profile_read(cap: int = 32):

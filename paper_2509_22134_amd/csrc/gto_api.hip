@@ -32,6 +32,7 @@ struct ProfRecord {
 constexpr size_t kProfInitialPairs = 1024, kProfMaxRecords = 16384;
 struct ProfState {
   bool on = false;
+  std::string only;      // empty: every kernel is timed; else only the kernel of this name
   std::vector<ProfRecord> used;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> free_pairs;
   size_t created = 0;
@@ -56,6 +57,7 @@ struct ProfScope {
   bool on;
   ProfRecord rec;
   ProfScope(const char *name, hipStream_t s) : st(s), on(t_prof.on) {
+    if (on && !t_prof.only.empty() && t_prof.only != name) on = false;
     if (!on) return;
     if (t_prof.free_pairs.empty() && !t_prof.grow(256)) { on = false; return; }
     if (t_prof.free_pairs.empty()) { on = false; return; }      // cap reached: this launch is not timed
@@ -1032,6 +1034,11 @@ int gto_calibration_copy(const void *src, void *dst, size_t bytes, void *hip_str
 int gto_profile_enable(int on) {
   if (on && t_prof.created == 0 && !t_prof.grow(kProfInitialPairs)) return hip_status();
   t_prof.on = (on != 0);
+  return GTO_OK;
+}
+
+int gto_profile_filter(const char *kernel_name_or_null) {
+  t_prof.only = kernel_name_or_null ? kernel_name_or_null : "";
   return GTO_OK;
 }
 

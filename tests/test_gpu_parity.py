@@ -322,6 +322,33 @@ def test_sampled_reading_of_the_longest_accepted_sequence(gpu_device, name, R, V
     _compare_ppo(w, tens, path)
 
 
+def test_kernel_timing_and_its_filter(gpu_device):
+    """The measurement aid: with timing on, every kernel of a step is reported once per launch; with the
+    filter set, only the named kernel is; the results of the step are the same either way."""
+    _say("per-kernel timing and its filter")
+    w = S.CONFIGS["tiny"]
+    tens = S.make_logits(w, gpu_device)
+    plain = _run_full(w, tens, gpu_device)
+    G.gto_profile_read()                                   # drop whatever an earlier test left
+    G.gto_profile_enable(True)
+    try:
+        timed = _run_full(w, tens, gpu_device)
+        everything = G.gto_profile_read()
+        G.gto_profile_filter("row_stats_draft")
+        only = _run_full(w, tens, gpu_device)
+        filtered = G.gto_profile_read()
+    finally:
+        G.gto_profile_filter(None)
+        G.gto_profile_enable(False)
+    assert {"row_stats_draft", "row_stats_target", "expand", "select_topg", "reward_path", "ppo_bwd"} <= set(everything)
+    assert everything["row_stats_draft"][0] == 2 and everything["row_stats_draft"][1] > 0.0      # two trees per root
+    assert set(filtered) == {"row_stats_draft"} and filtered["row_stats_draft"][0] == 2
+    for other in (timed, only):
+        assert torch.equal(plain.ppo["loss"], other.ppo["loss"]) and torch.equal(plain.grad_slot, other.grad_slot)
+    _run_full(w, tens, gpu_device)
+    assert G.gto_profile_read() == {}                      # timing off again: nothing recorded
+
+
 def test_step_can_be_captured_in_a_hip_graph(gpu_device):
     """The library allocates nothing, clears nothing with memset and never synchronises, so one step can
     be recorded into a HIP graph.  Every replay (with the inputs changed in place and eager work and

@@ -2,9 +2,10 @@
 // greedy verification walk, group advantage, clipped surrogate forward.  All of them work on a
 // few KB per root that live in LDS; they are latency-bound and tiny next to the row kernels.
 //
-// Ranking everywhere is "rank = number of keys that beat mine" on a packed 64-bit key
-// (order-preserving bits of the fp32 score, then inverted index), which is branch-free,
-// deterministic and realises (score descending, index ascending) exactly.
+// Ranking everywhere is on a packed 64-bit key (order-preserving bits of the fp32 score, then the
+// inverted index): keys are unique, so (score descending, index ascending) is realised exactly and
+// deterministically whether a rank is found by counting the keys that beat mine (expansion: k^2
+// keys per level) or by sorting (top-g: C keys).
 #include "gto_device.h"
 #include "gto_kernels.h"
 

@@ -205,6 +205,22 @@ def test_mid_size_full_path(gpu_device, name, R, V, kw):
     assert n_ambig <= max(2, R // 4)
 
 
+@pytest.mark.parametrize("k,d,g,V,dtype", [
+    (64, 1, 64, 4096, "bf16"),          # widest branching (one wave's list holds 64 entries); a single level
+    (63, 2, 4032, 1024, "f32"),         # largest pool two levels reach: C = 63 + 63^2 = 4032, every candidate kept
+    (11, 32, 500, 512, "bf16"),         # deepest tree (32 levels): C = 11 + 31 * 121 = 3762
+    (4, 2, 8, 2_000_000, "bf16"),       # a long row: 2 M logits (977 tiles of 2048, ragged tail of 1280)
+])
+def test_sizes_at_the_limits(gpu_device, k, d, g, V, dtype):
+    """The limits the header states (k <= 64, d <= 32, C <= 4096) and a vocabulary far beyond the paper's."""
+    _say(f"limits: k={k} d={d} g={g} V={V} {dtype}")
+    w = S.scaled(S.CONFIGS["llama31_8b"], R=2, V=V, k=k, d=d, g=g, m=2, dtype=dtype, n_peaks=min(32, V // 4))
+    tens = S.make_logits(w, gpu_device)
+    path = _run_full(w, tens, gpu_device)
+    _compare_all(w, tens, path)
+    _compare_ppo(w, tens, path)
+
+
 def test_reference_stats_recomputed_in_workspace_and_zero_fill(gpu_device):
     _say("ppo fwd without reference stats; zero fill")
     w = S.scaled(S.CONFIGS["llama31_8b"], R=16, V=9000)
